@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Throughput of the GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One step = one gemm_run over one batch of synthetic input (seeded, generated on
+the host, resident in HBM before the timed region).  Prints ONE JSON line with
+the throughput (TFLOP/s for matrix-core-bound shapes, GB/s for HBM-bound ones),
+the roofline fraction of the kernel measured with HIP events on the launch
+stream, and the CPU oracle timed on a bounded sample of the same workload.
+
+The timing loop follows the paper's protocol in spirit (App. "Benchmarking
+kernel runtime"): untimed warm-up, many launches between two synchronisations,
+and no result is cached or reused between launches (HBM-bound shapes rotate
+through several weight buffers so that the last-level cache cannot serve them).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+PEAK_MFMA_TFLOPS = 2516.6     # dense bf16/fp16: 256 CU x 4096 FLOP/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+PEAK_FP32_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="square_8192", choices=sorted(wl.WORKLOADS))
+    ap.add_argument("--config", default=None, help="tile configuration name (default: built-in choice)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def gpu_desc(g, w):
+    dt = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16}
+    lay = {"row": g.ROW_MAJOR, "col": g.COL_MAJOR}
+    return g.GemmDesc(w.M, w.N, w.K, dtype=dt[w.dtype], layout_a=lay[w.layout_a],
+                      layout_b=lay[w.layout_b], epilogue=g.EPILOGUES[w.epilogue], batch=w.batch)
+
+
+def cpu_baseline(w, A, B, bias, target_s, gpu_out):
+    """The CPU leg: time the oracle (as it stands) on a bounded sample (the first R
+    rows of the output, all N columns, full K; R from a small calibration run), and
+    check sampled entries of the GPU result of the last timed launch against it."""
+    import oracle
+    oracle.build()
+    dt = {"f32": oracle.DTYPE_F32, "bf16": oracle.DTYPE_BF16, "f16": oracle.DTYPE_F16}
+    lay = {"row": oracle.ROW_MAJOR, "col": oracle.COL_MAJOR}
+    epi = {"none": oracle.EPI_NONE, "bias": oracle.EPI_BIAS, "bias_relu": oracle.EPI_BIAS_RELU,
+           "bias_gelu_erf": oracle.EPI_BIAS_GELU_ERF, "bias_gelu_tanh": oracle.EPI_BIAS_GELU_TANH,
+           "relu": oracle.EPI_RELU, "gelu_erf": oracle.EPI_GELU_ERF}
+
+    def oracle_problem(o, x):
+        return o.Problem(x.M, x.N, x.K, dt[x.dtype], dt[x.dtype], lay[x.layout_a], lay[x.layout_b],
+                         epilogue=epi[x.epilogue], batch=x.batch)
+
+    a, b = wl.storage_numpy(A), wl.storage_numpy(B)
+    bz = None if bias is None else bias.numpy()
+
+    # sampled check of the GPU output: |C - y| within K u S (any-order fp32 accumulation of
+    # exact products) + epilogue slack + one rounding to the output type
+    pb, pi, pj = wl.sample_points(w, 2048, 99)
+    ref = oracle.ref_gemm_points(oracle_problem(oracle, w), a, b, bz, pb, pi, pj, want=("y", "t", "s"))
+    got = gpu_out.to(torch.float64).numpy()[pb, pi, pj]
+    u_out = {"bf16": 2.0 ** -9, "f16": 2.0 ** -11, "f32": 2.0 ** -24}[w.dtype]
+    acc = 1.13 * w.K * 2.0 ** -24 * ref["s"] + 16 * 2.0 ** -24 * (np.abs(ref["t"]) + 1.0)
+    bound = acc + u_out * (np.abs(ref["y"]) + acc) * 1.001 + 1e-30
+    matches = bool(np.all(np.abs(got - ref["y"]) <= bound))
+
+    def run(rows):
+        sub = wl.scaled(w, M=rows, batch=1)
+        p = oracle_problem(oracle, sub)
+        t0 = time.perf_counter()
+        oracle.ref_gemm(p, a, b, bz, want=("y",))
+        return time.perf_counter() - t0
+
+    cores = oracle.num_threads()
+    r0 = min(w.M, max(1, cores))
+    t_cal = run(r0)
+    per_row = max(t_cal / r0, 1e-9)
+    rows = int(min(w.M, max(r0, target_s / per_row)))
+    rows = max(cores, rows - rows % cores) if rows >= cores else rows
+    t = run(rows)
+    flops = 2.0 * rows * w.N * w.K
+    if w.bound == "hbm":
+        e = 2 if w.dtype != "f32" else 4
+        val, unit = e * (rows * w.K + w.K * w.N + rows * w.N) / t / 1e9, "GB/s"
+    else:
+        val, unit = flops / t / 1e12, "TFLOP/s"
+    return {"value": val, "unit": unit, "cores": cores, "kind": "oracle",
+            "gpu_output_matches_oracle_samples": matches,
+            "sample": f"first {rows} of {w.M} output rows x all {w.N} columns, full K={w.K}, "
+                      f"batch 0, fp64 triple loop, {t:.2f} s wall"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+    import paper_2603_12440_amd as g
+    g.load_library()                      # raises if the HIP library is missing
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = wl.WORKLOADS[args.workload]
+    A, B, bias = wl.make_inputs(w)
+    desc = gpu_desc(g, w)
+    cfg = -1 if args.config is None else g.config_names().index(args.config)
+    plan = g.gemm_create_config(desc, cfg)
+    info = plan.info()
+
+    # HBM-bound shapes: rotate through enough distinct copies of the operands that
+    # the 256 MB last-level cache cannot hold them (no reuse between launches).
+    nbuf = 1
+    if w.bound == "hbm":
+        nbuf = max(2, int(np.ceil(1.2e9 / w.bytes)))
+        nbuf = min(nbuf, 64)
+    Ad = [A.to(dev) for _ in range(nbuf)]
+    Bd = [B.to(dev) for _ in range(nbuf)]
+    odt = wl.TORCH_DTYPE[w.dtype]
+    Cd = [torch.empty((w.batch, w.M, w.N), dtype=odt, device=dev) for _ in range(nbuf)]
+    biasd = bias.to(dev) if bias is not None else None
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(i):
+        j = i % nbuf
+        g.gemm_run(plan, Ad[j], Bd[j], Cd[j], biasd, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    kern_ms = ev0.elapsed_time(ev1) / args.steps       # average launch duration on the launch stream
+
+    if w.bound == "hbm":
+        metric, unit = "HBM-bound GEMM throughput (algorithmic bytes / time)", "GB/s"
+        value = w.bytes / (ms_per_step * 1e-3) / 1e9
+        achieved, peak, bound, runit = w.bytes / (kern_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "hbm", "GB/s"
+    else:
+        metric, unit = "GEMM throughput (2MNK / time)", "TFLOP/s"
+        value = w.flops / (ms_per_step * 1e-3) / 1e12
+        peak = PEAK_FP32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_TFLOPS
+        achieved, bound, runit = w.flops / (kern_ms * 1e-3) / 1e12, ("alu" if w.dtype == "f32" else "mfma"), "TFLOP/s"
+
+    out = {
+        "metric": metric, "value": round(value, 3), "unit": unit, "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "batch": w.batch,
+                   "layout": f"A {w.layout_a}-major, B {w.layout_b}-major, C row-major",
+                   "epilogue": w.epilogue, "plan": info, "buffers_rotated": nbuf},
+        "roofline": {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": runit,
+                     "frac": round(achieved / peak, 4), "traffic": None},
+    }
+    ok = True
+    if not args.no_cpu_baseline:
+        # the paper's "no result reuse" rule: the last timed launch's output is checked
+        last = Cd[(args.steps - 1) % nbuf].cpu()
+        out["cpu_baseline"] = cpu_baseline(w, A, B, bias, args.cpu_seconds, last)
+        ok = out["cpu_baseline"]["gpu_output_matches_oracle_samples"]
+    g.gemm_destroy(plan)
+    print(json.dumps(out))
+    return 0 if ok else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,133 @@
+/*
+ * mi355gemm - dense matrix product with a fused epilogue for AMD MI355X (gfx950).
+ *
+ *     C[b] = act( A[b] . B[b] + bias )        b = 0 .. batch-1
+ *
+ * A is M x K, B is K x N, C is M x N (logical shapes).  Products are
+ * accumulated in fp32 whatever the storage type; the epilogue runs in fp32 on
+ * the accumulators and the result is rounded once (to nearest even) to C's
+ * storage type.  The operation is the matmul-with-post-op workload class of
+ * the paper's evaluation (Sec. 4, Tab. "operations": "Matmul with relu
+ * post-op"; App. "Per-task results": matmul + GELU / activation tasks,
+ * matrix-vector product, FFN-shaped layers).  The paper fixes no GEMM problem
+ * statement; the definition above is the textbook one.
+ *
+ * Plain C ABI: no exceptions, no C++ or torch types cross this boundary.
+ * All matrix pointers are DEVICE pointers; descriptors and plans live on the
+ * HOST.  The library never allocates device memory, never synchronises the
+ * device and keeps no state between calls besides the plans it hands out.
+ */
+#ifndef MI355GEMM_GEMM_H
+#define MI355GEMM_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gemm_plan gemm_plan_t;          /* opaque, owned by the library */
+
+typedef enum { GEMM_F32 = 0, GEMM_BF16 = 1, GEMM_F16 = 2 } gemm_dtype_t;
+typedef enum { GEMM_ROW_MAJOR = 0, GEMM_COL_MAJOR = 1 } gemm_layout_t;
+
+/* Epilogues.  bias is a length-N fp32 vector added to every row (one value per
+ * output column), before the activation.
+ *   GELU_ERF (t) = t/2 * (1 + erf(t / sqrt 2))
+ *   GELU_TANH(t) = t/2 * (1 + tanh(sqrt(2/pi) * (t + 0.044715 t^3)))          */
+typedef enum {
+  GEMM_EPI_NONE = 0,
+  GEMM_EPI_BIAS = 1,
+  GEMM_EPI_BIAS_RELU = 2,
+  GEMM_EPI_BIAS_GELU_ERF = 3,
+  GEMM_EPI_BIAS_GELU_TANH = 4,
+  GEMM_EPI_RELU = 5,
+  GEMM_EPI_GELU_ERF = 6
+} gemm_epilogue_t;
+
+/* Status codes: 0 is success, every failure is negative. */
+enum {
+  GEMM_OK = 0,
+  GEMM_ERR_NULL = -1,         /* a required pointer is NULL (or bias given/absent against the epilogue) */
+  GEMM_ERR_BAD_DIM = -2,      /* M, N or K <= 0, batch < 1, or sizes beyond the supported range */
+  GEMM_ERR_BAD_LD = -3,       /* leading dimension below the extent, or batch stride overlapping */
+  GEMM_ERR_UNSUPPORTED = -4,  /* no kernel for this dtype / layout / epilogue combination */
+  GEMM_ERR_MISALIGNED = -5,   /* pointer not aligned to the element size */
+  GEMM_ERR_NO_DEVICE = -6,    /* current device is not a gfx950 GPU */
+  GEMM_ERR_LAUNCH = -7,       /* the HIP runtime refused the launch */
+  GEMM_ERR_BAD_ENUM = -8,     /* an enum field holds a value outside its range */
+  GEMM_ERR_BAD_CONFIG = -9    /* tile configuration index unknown or not applicable */
+};
+
+/*
+ * Problem descriptor (host memory, read only during gemm_create).
+ *
+ * Addressing, in elements of the operand's storage type:
+ *   A(i,k) = A[b*stride_a + i*lda + k]   row-major,   A[b*stride_a + k*lda + i]   column-major
+ *   B(k,j) = B[b*stride_b + k*ldb + j]   row-major,   B[b*stride_b + j*ldb + k]   column-major
+ *   C(i,j) = C[b*stride_c + i*ldc + j]   row-major,   C[b*stride_c + j*ldc + i]   column-major
+ *   bias(j) = bias[b*stride_bias + j]
+ * A leading dimension of 0 means packed (the minor extent); a batch stride of 0
+ * means packed for A, B and C (ld * major extent) and "shared by all batches"
+ * for the bias.  Elements of the padding between rows are neither read into
+ * results nor written.
+ */
+typedef struct {
+  int64_t M, N, K;
+  int32_t layout_a, layout_b, layout_c;          /* gemm_layout_t */
+  int64_t lda, ldb, ldc;
+  int32_t dtype_a, dtype_b, dtype_c, dtype_bias; /* gemm_dtype_t; dtype_a == dtype_b; dtype_c is dtype_a or F32; bias F32 */
+  int32_t epilogue;                              /* gemm_epilogue_t */
+  int32_t batch;                                 /* >= 1 */
+  int64_t stride_a, stride_b, stride_c, stride_bias;
+} gemm_desc_t;
+
+/*
+ * gemm_create - validate a descriptor and choose kernel, tile shape and grid.
+ * Runs entirely on the host and touches no device.  On success *out_plan
+ * receives a new plan (release with gemm_destroy); on failure it is set to NULL
+ * and nothing is allocated.  The kernel is picked from a fixed table of
+ * compiled tile instantiations, in the manner of the paper's templated kernels
+ * with a dispatch function (Sec. 3.4, App. "Templated kernel" listing).
+ */
+int gemm_create(const gemm_desc_t* desc, gemm_plan_t** out_plan);
+
+/*
+ * gemm_create_config - as gemm_create, but with tile configuration `config`
+ * (0 .. gemm_config_count()-1) instead of the built-in choice; -1 = built-in
+ * choice.  Returns GEMM_ERR_BAD_CONFIG if that instantiation cannot run this
+ * problem.  This is the hook for parameter tuning (Sec. 3.4): time every
+ * applicable configuration, keep the best.
+ */
+int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_plan);
+int gemm_config_count(void);
+const char* gemm_config_name(int config);      /* NULL if out of range; static storage */
+
+/*
+ * gemm_run - enqueue one product on `hip_stream` (a hipStream_t cast to void*;
+ * NULL = the default stream) of the current device and return without waiting.
+ * A, B, C, bias: device pointers laid out as the plan's descriptor says, owned
+ * by the caller; A, B and bias are only read, C is only written and must not
+ * overlap A or B.  bias must be non-NULL exactly when the epilogue has a bias.
+ * Every call recomputes everything; nothing is cached between calls.  A plan is
+ * immutable: it may be shared by threads and streams.
+ */
+int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C,
+             const void* bias, void* hip_stream);
+
+/* gemm_destroy - release a plan.  NULL is a no-op that returns GEMM_OK. */
+int gemm_destroy(gemm_plan_t* plan);
+
+/* Static, human-readable text for a status code (never NULL). */
+const char* gemm_status_string(int status);
+
+/* Writes "kernel=<name> tile=<BM>x<BN>x<BK> grid=<x>,<y>,<z> block=<t> lds=<bytes>"
+ * (NUL-terminated, truncated to n bytes) into buf; returns the untruncated length
+ * or a negative status. */
+int gemm_plan_info(const gemm_plan_t* plan, char* buf, size_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355GEMM_GEMM_H */

@@ -1,0 +1,178 @@
+"""ctypes binding of include/gemm.h: same names, argument marshalling only.
+
+There is no fallback: if libmi355gemm.so is missing or does not load, every
+entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libmi355gemm.so")
+
+F32, BF16, F16 = 0, 1, 2
+ROW_MAJOR, COL_MAJOR = 0, 1
+(EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
+ EPI_RELU, EPI_GELU_ERF) = range(7)
+EPILOGUES = {"none": EPI_NONE, "bias": EPI_BIAS, "bias_relu": EPI_BIAS_RELU,
+             "bias_gelu_erf": EPI_BIAS_GELU_ERF, "bias_gelu_tanh": EPI_BIAS_GELU_TANH,
+             "relu": EPI_RELU, "gelu_erf": EPI_GELU_ERF}
+
+GEMM_OK = 0
+
+
+class GemmError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"gemm status {status}: {text}")
+        self.status = status
+
+
+class GemmDesc(ctypes.Structure):
+    """Mirror of gemm_desc_t."""
+    _fields_ = [
+        ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+        ("layout_a", ctypes.c_int32), ("layout_b", ctypes.c_int32), ("layout_c", ctypes.c_int32),
+        ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64), ("ldc", ctypes.c_int64),
+        ("dtype_a", ctypes.c_int32), ("dtype_b", ctypes.c_int32), ("dtype_c", ctypes.c_int32),
+        ("dtype_bias", ctypes.c_int32),
+        ("epilogue", ctypes.c_int32), ("batch", ctypes.c_int32),
+        ("stride_a", ctypes.c_int64), ("stride_b", ctypes.c_int64), ("stride_c", ctypes.c_int64),
+        ("stride_bias", ctypes.c_int64),
+    ]
+
+    def __init__(self, M=0, N=0, K=0, dtype=BF16, layout_a=ROW_MAJOR, layout_b=COL_MAJOR,
+                 layout_c=ROW_MAJOR, lda=0, ldb=0, ldc=0, dtype_c=None, epilogue=EPI_NONE,
+                 batch=1, stride_a=0, stride_b=0, stride_c=0, stride_bias=0,
+                 dtype_b=None, dtype_bias=F32):
+        super().__init__(M, N, K, layout_a, layout_b, layout_c, lda, ldb, ldc,
+                         dtype, dtype if dtype_b is None else dtype_b,
+                         dtype if dtype_c is None else dtype_c, dtype_bias,
+                         epilogue, batch, stride_a, stride_b, stride_c, stride_bias)
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libmi355gemm.so (built by paper_2603_12440_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it first "
+                           "(python -m paper_2603_12440_amd.build); there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    lib.gemm_create.restype = ctypes.c_int
+    lib.gemm_create.argtypes = [ctypes.POINTER(GemmDesc), pp]
+    lib.gemm_create_config.restype = ctypes.c_int
+    lib.gemm_create_config.argtypes = [ctypes.POINTER(GemmDesc), ctypes.c_int, pp]
+    lib.gemm_config_count.restype = ctypes.c_int
+    lib.gemm_config_name.restype = ctypes.c_char_p
+    lib.gemm_config_name.argtypes = [ctypes.c_int]
+    lib.gemm_run.restype = ctypes.c_int
+    lib.gemm_run.argtypes = [ctypes.c_void_p] * 6
+    lib.gemm_destroy.restype = ctypes.c_int
+    lib.gemm_destroy.argtypes = [ctypes.c_void_p]
+    lib.gemm_status_string.restype = ctypes.c_char_p
+    lib.gemm_status_string.argtypes = [ctypes.c_int]
+    lib.gemm_plan_info.restype = ctypes.c_int
+    lib.gemm_plan_info.argtypes = [ctypes.c_void_p, ctypes.c_char_p, ctypes.c_size_t]
+    _lib = lib
+    return lib
+
+
+def gemm_status_string(status: int) -> str:
+    return load_library().gemm_status_string(status).decode()
+
+
+def _check(status: int):
+    if status != GEMM_OK:
+        raise GemmError(status, gemm_status_string(status))
+
+
+class Plan:
+    """Owns one gemm_plan_t*; destroyed with the object (or by gemm_destroy)."""
+
+    def __init__(self, handle: int, desc: GemmDesc):
+        self.handle = handle
+        self.desc = desc
+
+    def info(self) -> str:
+        return gemm_plan_info(self)
+
+    def close(self):
+        if self.handle:
+            load_library().gemm_destroy(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gemm_create_config(desc: GemmDesc, config: int = -1) -> Plan:
+    lib = load_library()
+    out = ctypes.c_void_p()
+    _check(lib.gemm_create_config(ctypes.byref(desc), config, ctypes.byref(out)))
+    return Plan(out.value, desc)
+
+
+def gemm_create(desc: GemmDesc) -> Plan:
+    lib = load_library()
+    out = ctypes.c_void_p()
+    _check(lib.gemm_create(ctypes.byref(desc), ctypes.byref(out)))
+    return Plan(out.value, desc)
+
+
+def _dev_ptr(x) -> Optional[int]:
+    """Device address of a torch tensor (or a raw integer address, or None)."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def gemm_run(plan: Plan, A, B, C, bias=None, stream: Optional[int] = None) -> None:
+    """Enqueue C = epilogue(A.B) on `stream` (a raw hipStream_t value; default:
+    torch's current stream).  A, B, C, bias: torch device tensors or raw addresses."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(load_library().gemm_run(plan.handle, _dev_ptr(A), _dev_ptr(B), _dev_ptr(C),
+                                   _dev_ptr(bias), stream or None))
+
+
+def gemm_destroy(plan: Optional[Plan]) -> None:
+    if plan is not None:
+        plan.close()
+
+
+def gemm_plan_info(plan: Plan) -> str:
+    buf = ctypes.create_string_buffer(256)
+    n = load_library().gemm_plan_info(plan.handle, buf, len(buf))
+    if n < 0:
+        _check(n)
+    return buf.value.decode()
+
+
+def gemm_config_count() -> int:
+    return load_library().gemm_config_count()
+
+
+def gemm_config_name(config: int) -> Optional[str]:
+    s = load_library().gemm_config_name(config)
+    return s.decode() if s is not None else None
+
+
+def config_names() -> List[str]:
+    return [gemm_config_name(i) for i in range(gemm_config_count())]

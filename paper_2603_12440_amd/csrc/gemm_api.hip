@@ -1,0 +1,393 @@
+// Host side of the mi355gemm C ABI (include/gemm.h): descriptor validation, the
+// table of compiled kernel instantiations, the choice among them, and launches.
+//
+// The table-plus-dispatcher shape follows the paper's templated kernels
+// (Sec. 3.4 and the templated-kernel example in the appendix): every tile
+// shape is a template instantiation, a dispatch function maps integer
+// parameters to the instantiation, and a tuner may time each applicable one.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "../../include/gemm.h"
+#include "common.hpp"
+#include "mfma_kernel.hpp"
+#include "simt_kernel.hpp"
+#include "skinny_kernel.hpp"
+
+using namespace mi355gemm;
+
+namespace {
+
+enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2 };
+
+struct Config;
+
+}  // namespace
+
+struct gemm_plan {
+  gemm_desc_t d;          // fully resolved (no zero ld / stride left)
+  const Config* cfg;
+  int cfg_index;
+  dim3 grid, block;
+  int group_m, xcd_remap; // MFMA scheduling
+};
+
+namespace {
+
+typedef hipError_t (*launch_fn)(const gemm_plan&, const void*, const void*, void*, const void*,
+                                hipStream_t);
+
+struct Config {
+  const char* name;
+  Kind kind;
+  int bm, bn, bk;         // tile (skinny: bm = padded M, bn = rows of W per wave, bk = 512)
+  int threads;
+  int lds_bytes;
+  launch_fn launch[3];    // per storage dtype (GEMM_F32 / BF16 / F16); NULL = not compiled
+};
+
+inline int esize(int dt) { return dt == GEMM_F32 ? 4 : 2; }
+
+// ---- launchers ---------------------------------------------------------------------
+
+template <typename TIn, typename TOut, int TM, int TN, int TK>
+hipError_t launch_simt_typed(const gemm_plan& pl, const void* A, const void* B, void* C,
+                             const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  SimtArgs a;
+  a.A = A; a.B = B; a.C = C; a.bias = (const float*)bias;
+  a.M = d.M; a.N = d.N; a.K = d.K;
+  a.a_si = d.layout_a == GEMM_ROW_MAJOR ? d.lda : 1;
+  a.a_sk = d.layout_a == GEMM_ROW_MAJOR ? 1 : d.lda;
+  a.b_sk = d.layout_b == GEMM_ROW_MAJOR ? d.ldb : 1;
+  a.b_sj = d.layout_b == GEMM_ROW_MAJOR ? 1 : d.ldb;
+  a.c_si = d.layout_c == GEMM_ROW_MAJOR ? d.ldc : 1;
+  a.c_sj = d.layout_c == GEMM_ROW_MAJOR ? 1 : d.ldc;
+  a.stride_a = d.stride_a; a.stride_b = d.stride_b; a.stride_c = d.stride_c;
+  a.stride_bias = d.stride_bias;
+  a.has_bias = epilogue_has_bias(d.epilogue);
+  a.act = epilogue_activation(d.epilogue);
+  simt_gemm_kernel<TIn, TOut, TM, TN, TK><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+template <typename TIn, int TM, int TN, int TK>
+hipError_t launch_simt(const gemm_plan& pl, const void* A, const void* B, void* C,
+                       const void* bias, hipStream_t s) {
+  if (pl.d.dtype_c == GEMM_F32)
+    return launch_simt_typed<TIn, float, TM, TN, TK>(pl, A, B, C, bias, s);
+  return launch_simt_typed<TIn, TIn, TM, TN, TK>(pl, A, B, C, bias, s);
+}
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, int NS>
+hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
+                       const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  MfmaArgs a;
+  a.A = A; a.B = B; a.C = C; a.bias = (const float*)bias;
+  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
+  a.lda = d.lda; a.ldb = d.ldb; a.ldc = d.ldc;
+  a.stride_a = d.stride_a; a.stride_b = d.stride_b; a.stride_c = d.stride_c;
+  a.stride_bias = d.stride_bias;
+  a.has_bias = epilogue_has_bias(d.epilogue);
+  a.act = epilogue_activation(d.epilogue);
+  a.c_f32 = d.dtype_c == GEMM_F32;
+  a.tiles_m = (int)((d.M + BM - 1) / BM);
+  a.tiles_n = (int)((d.N + BN - 1) / BN);
+  a.group_m = pl.group_m;
+  a.xcd_remap = pl.xcd_remap;
+  mfma_gemm_kernel<T, BM, BN, BK, WM, WN, NS><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+template <typename T, int MB, int RPW, int WAVES>
+hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void* C,
+                         const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  SkinnyArgs a;
+  a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
+  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
+  a.ldx = d.lda; a.ldw = d.ldb; a.ldy = d.ldc;
+  a.stride_x = d.stride_a; a.stride_w = d.stride_b; a.stride_y = d.stride_c;
+  a.stride_bias = d.stride_bias;
+  a.has_bias = epilogue_has_bias(d.epilogue);
+  a.act = epilogue_activation(d.epilogue);
+  a.y_f32 = d.dtype_c == GEMM_F32;
+  skinny_gemm_kernel<T, MB, RPW, WAVES><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+// ---- the table of compiled instantiations ----------------------------------------------
+
+#define SIMT_CFG(TM, TN, TK)                                                               \
+  { "simt_" #TM "x" #TN "x" #TK, KIND_SIMT, TM, TN, TK, 256,                               \
+    (int)(sizeof(float) * TK * (TM + 4 + TN + 4)),                                         \
+    { launch_simt<float, TM, TN, TK>, launch_simt<bf16_t, TM, TN, TK>,                     \
+      launch_simt<f16_t, TM, TN, TK> } }
+
+#define MFMA_CFG(BM, BN, BK, WM, WN, NS)                                                   \
+  { "mfma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, KIND_MFMA, BM, BN, BK,          \
+    64 * WM * WN, MfmaTile<bf16_t, BM, BN, BK, WM, WN, NS>::LDS_BYTES,                     \
+    { nullptr, launch_mfma<bf16_t, BM, BN, BK, WM, WN, NS>,                                \
+      launch_mfma<f16_t, BM, BN, BK, WM, WN, NS> } }
+
+#define SKINNY_CFG(MB, RPW, WAVES)                                                         \
+  { "skinny_m" #MB "_r" #RPW "_w" #WAVES, KIND_SKINNY, MB, RPW, 512, 64 * WAVES, 0,        \
+    { nullptr, launch_skinny<bf16_t, MB, RPW, WAVES>, launch_skinny<f16_t, MB, RPW, WAVES> } }
+
+const Config kConfigs[] = {
+    SIMT_CFG(64, 64, 16),
+    SIMT_CFG(32, 32, 16),
+    MFMA_CFG(256, 256, 64, 2, 2, 2),
+    MFMA_CFG(256, 256, 32, 2, 2, 4),
+    MFMA_CFG(256, 256, 64, 2, 4, 2),
+    MFMA_CFG(256, 128, 64, 2, 2, 2),
+    MFMA_CFG(128, 128, 64, 2, 2, 2),
+    SKINNY_CFG(1, 4, 4),
+    SKINNY_CFG(2, 4, 4),
+    SKINNY_CFG(4, 4, 4),
+    SKINNY_CFG(8, 2, 4),
+    SKINNY_CFG(16, 1, 4),
+};
+constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
+
+constexpr int kNumCUs = 256;   // MI355X
+
+// ---- validation -----------------------------------------------------------------------
+
+bool in_range(int v, int lo, int hi) { return v >= lo && v <= hi; }
+
+// Resolve packed (0) leading dimensions / strides and check every field.
+int resolve(const gemm_desc_t* in, gemm_desc_t* out) {
+  gemm_desc_t d = *in;
+  if (!in_range(d.layout_a, 0, 1) || !in_range(d.layout_b, 0, 1) || !in_range(d.layout_c, 0, 1) ||
+      !in_range(d.dtype_a, 0, 2) || !in_range(d.dtype_b, 0, 2) || !in_range(d.dtype_c, 0, 2) ||
+      !in_range(d.dtype_bias, 0, 2) || !in_range(d.epilogue, 0, GEMM_EPI_GELU_ERF))
+    return GEMM_ERR_BAD_ENUM;
+  if (d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch < 1) return GEMM_ERR_BAD_DIM;
+  const int64_t kMaxDim = (int64_t)1 << 30;
+  if (d.M > kMaxDim || d.N > kMaxDim || d.K > kMaxDim || d.batch > 65535) return GEMM_ERR_BAD_DIM;
+  if (d.lda < 0 || d.ldb < 0 || d.ldc < 0 || d.stride_a < 0 || d.stride_b < 0 ||
+      d.stride_c < 0 || d.stride_bias < 0)
+    return GEMM_ERR_BAD_LD;
+
+  const int64_t a_minor = d.layout_a == GEMM_ROW_MAJOR ? d.K : d.M;
+  const int64_t a_major = d.layout_a == GEMM_ROW_MAJOR ? d.M : d.K;
+  const int64_t b_minor = d.layout_b == GEMM_ROW_MAJOR ? d.N : d.K;
+  const int64_t b_major = d.layout_b == GEMM_ROW_MAJOR ? d.K : d.N;
+  const int64_t c_minor = d.layout_c == GEMM_ROW_MAJOR ? d.N : d.M;
+  const int64_t c_major = d.layout_c == GEMM_ROW_MAJOR ? d.M : d.N;
+  if (d.lda == 0) d.lda = a_minor;
+  if (d.ldb == 0) d.ldb = b_minor;
+  if (d.ldc == 0) d.ldc = c_minor;
+  if (d.lda < a_minor || d.ldb < b_minor || d.ldc < c_minor) return GEMM_ERR_BAD_LD;
+  const int64_t kMaxLd = (int64_t)1 << 40;
+  if (d.lda > kMaxLd || d.ldb > kMaxLd || d.ldc > kMaxLd) return GEMM_ERR_BAD_LD;
+  const int64_t a_span = (a_major - 1) * d.lda + a_minor;
+  const int64_t b_span = (b_major - 1) * d.ldb + b_minor;
+  const int64_t c_span = (c_major - 1) * d.ldc + c_minor;
+  if (d.stride_a == 0) d.stride_a = a_major * d.lda;
+  if (d.stride_b == 0) d.stride_b = b_major * d.ldb;
+  if (d.stride_c == 0) d.stride_c = c_major * d.ldc;
+  if (d.batch > 1) {
+    // Reading one A or B slab for several batches would be legal, but the stride
+    // field uses 0 for "packed", so overlapping inputs are not expressible; an
+    // overlapping output is always an error.
+    if (d.stride_a < a_span || d.stride_b < b_span || d.stride_c < c_span) return GEMM_ERR_BAD_LD;
+    if (d.stride_bias != 0 && d.stride_bias < d.N) return GEMM_ERR_BAD_LD;
+  }
+  if (d.dtype_a != d.dtype_b) return GEMM_ERR_UNSUPPORTED;
+  if (d.dtype_c != d.dtype_a && d.dtype_c != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
+  if (d.dtype_bias != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
+  *out = d;
+  return GEMM_OK;
+}
+
+// Can instantiation c run problem d?
+bool applicable(const Config& c, const gemm_desc_t& d) {
+  if (!c.launch[d.dtype_a]) return false;
+  if (c.kind == KIND_SIMT) return true;
+  // The MFMA and skinny kernels take K-contiguous A and B, row-major C, and move
+  // 16-byte pieces: every row start must be 16-byte aligned.
+  if (d.layout_a != GEMM_ROW_MAJOR || d.layout_b != GEMM_COL_MAJOR || d.layout_c != GEMM_ROW_MAJOR)
+    return false;
+  if (d.K % 8 || d.lda % 8 || d.ldb % 8 || d.stride_a % 8 || d.stride_b % 8) return false;
+  if (d.M >= ((int64_t)1 << 31) - 512 || d.N >= ((int64_t)1 << 31) - 512 ||
+      d.K >= ((int64_t)1 << 31) - 512)
+    return false;
+  if (c.kind == KIND_SKINNY) return d.M <= c.bm;
+  // MFMA: per-lane byte offsets inside a tile's row panel are 32-bit.
+  if ((int64_t)c.bm * d.lda * 2 >= ((int64_t)1 << 32) || (int64_t)c.bn * d.ldb * 2 >= ((int64_t)1 << 32))
+    return false;
+  const int64_t tiles = ((d.M + c.bm - 1) / c.bm) * ((d.N + c.bn - 1) / c.bn);
+  return tiles < ((int64_t)1 << 31);
+}
+
+int find_config(const char* name) {
+  for (int i = 0; i < kNumConfigs; ++i)
+    if (!std::strcmp(kConfigs[i].name, name)) return i;
+  return -1;
+}
+
+// Built-in choice.  MFMA tile: the largest tile whose grid still fills the 256 CUs
+// in whole rounds reasonably well (wave quantisation), biggest tile on ties.
+int choose(const gemm_desc_t& d) {
+  // skinny: smallest padded M that fits
+  if (d.M <= 16) {
+    int best = -1;
+    for (int i = 0; i < kNumConfigs; ++i)
+      if (kConfigs[i].kind == KIND_SKINNY && applicable(kConfigs[i], d) &&
+          (best < 0 || kConfigs[i].bm < kConfigs[best].bm))
+        best = i;
+    if (best >= 0) return best;
+  }
+  int best = -1;
+  double best_cost = 0;
+  for (int i = 0; i < kNumConfigs; ++i) {
+    const Config& c = kConfigs[i];
+    if (c.kind != KIND_MFMA || !applicable(c, d)) continue;
+    const double tiles = (double)((d.M + c.bm - 1) / c.bm) * (double)((d.N + c.bn - 1) / c.bn) * d.batch;
+    const double rounds = (double)(int64_t)((tiles + kNumCUs - 1) / kNumCUs);
+    // time ~ rounds * tile work / per-tile efficiency (bigger tiles reuse operands better)
+    const double eff = c.bm * c.bn >= 256 * 256 ? 1.0 : (c.bm * c.bn >= 256 * 128 ? 0.85 : 0.7);
+    const double cost = rounds * c.bm * c.bn / eff;
+    if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
+  }
+  if (best >= 0) return best;
+  // general kernel: small tile for small problems so that more CUs get work
+  const int big = find_config("simt_64x64x16"), small = find_config("simt_32x32x16");
+  const double tiles64 = (double)((d.M + 63) / 64) * (double)((d.N + 63) / 64) * d.batch;
+  return tiles64 >= kNumCUs ? big : small;
+}
+
+int fill_launch_shape(gemm_plan& pl) {
+  const gemm_desc_t& d = pl.d;
+  const Config& c = *pl.cfg;
+  pl.block = dim3(c.threads, 1, 1);
+  pl.group_m = 1;
+  pl.xcd_remap = 0;
+  if (c.kind == KIND_SIMT) {
+    const int64_t gx = (d.N + c.bn - 1) / c.bn, gy = (d.M + c.bm - 1) / c.bm;
+    if (gy > 65535) return GEMM_ERR_BAD_DIM;   // grid.y / grid.z limits
+    pl.grid = dim3((unsigned)gx, (unsigned)gy, (unsigned)d.batch);
+  } else if (c.kind == KIND_MFMA) {
+    const int64_t tm = (d.M + c.bm - 1) / c.bm, tn = (d.N + c.bn - 1) / c.bn;
+    pl.grid = dim3((unsigned)(tm * tn), (unsigned)d.batch, 1);
+    pl.group_m = (int)(tm < 8 ? tm : 8);
+    pl.xcd_remap = ((tm * tn) % 8 == 0) ? 1 : 0;
+  } else {
+    const int waves = c.threads / 64;
+    const int64_t groups = (d.N + c.bn - 1) / c.bn;
+    int64_t wgs = (groups + waves - 1) / waves;
+    const int64_t cap = (int64_t)kNumCUs * 8;        // grid-stride beyond this
+    if (wgs > cap) wgs = cap;
+    pl.grid = dim3((unsigned)wgs, (unsigned)d.batch, 1);
+  }
+  return GEMM_OK;
+}
+
+// gfx950 check, once per device.
+std::atomic<int> g_dev_ok[64];   // 0 unknown, 1 ok, -1 not gfx950
+
+int check_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) { (void)hipGetLastError(); return GEMM_ERR_NO_DEVICE; }
+  if (dev >= 64) return GEMM_ERR_NO_DEVICE;
+  int st = g_dev_ok[dev].load(std::memory_order_acquire);
+  if (st == 0) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_NO_DEVICE; }
+    st = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+    g_dev_ok[dev].store(st, std::memory_order_release);
+  }
+  return st == 1 ? GEMM_OK : GEMM_ERR_NO_DEVICE;
+}
+
+}  // namespace
+
+// ---- C ABI -------------------------------------------------------------------------------
+
+extern "C" {
+
+int gemm_config_count(void) { return kNumConfigs; }
+
+const char* gemm_config_name(int config) {
+  return (config >= 0 && config < kNumConfigs) ? kConfigs[config].name : nullptr;
+}
+
+int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_plan) {
+  if (out_plan) *out_plan = nullptr;
+  if (!desc || !out_plan) return GEMM_ERR_NULL;
+  gemm_desc_t d;
+  int rc = resolve(desc, &d);
+  if (rc != GEMM_OK) return rc;
+  if (config < -1 || config >= kNumConfigs) return GEMM_ERR_BAD_CONFIG;
+  if (config == -1) config = choose(d);
+  if (config < 0) return GEMM_ERR_UNSUPPORTED;
+  if (!applicable(kConfigs[config], d)) return GEMM_ERR_BAD_CONFIG;
+  gemm_plan* pl = new (std::nothrow) gemm_plan;
+  if (!pl) return GEMM_ERR_NULL;
+  pl->d = d;
+  pl->cfg = &kConfigs[config];
+  pl->cfg_index = config;
+  rc = fill_launch_shape(*pl);
+  if (rc != GEMM_OK) { delete pl; return rc; }
+  *out_plan = pl;
+  return GEMM_OK;
+}
+
+int gemm_create(const gemm_desc_t* desc, gemm_plan_t** out_plan) {
+  return gemm_create_config(desc, -1, out_plan);
+}
+
+int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, const void* bias,
+             void* hip_stream) {
+  if (!plan || !A || !B || !C) return GEMM_ERR_NULL;
+  const gemm_desc_t& d = plan->d;
+  if (epilogue_has_bias(d.epilogue) != (bias != nullptr)) return GEMM_ERR_NULL;
+  // The tiled 16-bit kernels move 16-byte pieces; the general kernel only needs
+  // element alignment.
+  const uintptr_t in_mask = plan->cfg->kind == KIND_SIMT ? (uintptr_t)esize(d.dtype_a) - 1 : 15;
+  if (((uintptr_t)A & in_mask) || ((uintptr_t)B & in_mask) ||
+      ((uintptr_t)C & ((uintptr_t)esize(d.dtype_c) - 1)) || ((uintptr_t)bias & 3))
+    return GEMM_ERR_MISALIGNED;
+  int rc = check_device();
+  if (rc != GEMM_OK) return rc;
+  hipError_t e = plan->cfg->launch[d.dtype_a](*plan, A, B, C, bias, (hipStream_t)hip_stream);
+  return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
+}
+
+int gemm_destroy(gemm_plan_t* plan) {
+  delete plan;
+  return GEMM_OK;
+}
+
+const char* gemm_status_string(int status) {
+  switch (status) {
+    case GEMM_OK: return "ok";
+    case GEMM_ERR_NULL: return "null pointer (or bias does not match the epilogue)";
+    case GEMM_ERR_BAD_DIM: return "bad dimension";
+    case GEMM_ERR_BAD_LD: return "bad leading dimension or batch stride";
+    case GEMM_ERR_UNSUPPORTED: return "unsupported dtype / layout / epilogue combination";
+    case GEMM_ERR_MISALIGNED: return "misaligned pointer";
+    case GEMM_ERR_NO_DEVICE: return "current device is not a gfx950 GPU";
+    case GEMM_ERR_LAUNCH: return "kernel launch failed";
+    case GEMM_ERR_BAD_ENUM: return "enum value out of range";
+    case GEMM_ERR_BAD_CONFIG: return "tile configuration unknown or not applicable";
+    default: return "unknown status";
+  }
+}
+
+int gemm_plan_info(const gemm_plan_t* plan, char* buf, size_t n) {
+  if (!plan || (!buf && n)) return GEMM_ERR_NULL;
+  const Config& c = *plan->cfg;
+  return std::snprintf(buf, n, "kernel=%s tile=%dx%dx%d grid=%u,%u,%u block=%u lds=%d", c.name,
+                       c.bm, c.bn, c.bk, plan->grid.x, plan->grid.y, plan->grid.z, plan->block.x,
+                       c.lds_bytes);
+}
+
+}  // extern "C"

@@ -1,0 +1,390 @@
+// Matrix-core GEMM for gfx950: 16-bit operands (bf16 / fp16), fp32 accumulate.
+//
+//   C = act(A . B + bias),  A row-major (K contiguous), B column-major (K
+//   contiguous: the "weight" matrix stored N x K), C row-major.
+//
+// One workgroup of WM x WN wavefronts owns a BM x BN block of C.  Per K-step of
+// BK columns the A and B slabs go global -> LDS with 16-byte direct-to-LDS
+// loads (no VGPR staging), NSTAGE slabs deep; wavefronts read MFMA fragments
+// with 16-byte LDS reads from an XOR-swizzled layout and issue
+// v_mfma_f32_32x32x16 on a (BM/WM) x (BN/WN) register block of accumulators.
+// The epilogue (bias, activation, rounding) runs on the accumulators in
+// registers.  Paper taxonomy (Sec. 3.2): d_mem = 3 (local-memory tiling +
+// register blocking + prefetch), d_algo = 1 (fused post-op), d_sync = 1.
+#pragma once
+
+#include <type_traits>
+
+#include "common.hpp"
+
+namespace mi355gemm {
+
+struct MfmaArgs {
+  const void* A; const void* B; void* C; const float* bias;
+  int M, N, K;
+  int64_t lda, ldb, ldc;                               // elements
+  int64_t stride_a, stride_b, stride_c, stride_bias;   // elements between batches
+  int has_bias, act, c_f32;
+  int tiles_m, tiles_n;        // ceil(M/BM), ceil(N/BN)
+  int group_m;                 // tile rows per scheduling group
+  int xcd_remap;               // 1: spread consecutive tile ids within one XCD
+};
+
+// ---- MFMA wrappers -----------------------------------------------------------
+template <typename T> struct Frag;
+template <> struct Frag<bf16_t> {
+  typedef bf16x8_t type;
+  static __device__ __forceinline__ f32x16_t mfma(type x, type y, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, c, 0, 0, 0);
+  }
+};
+template <> struct Frag<f16_t> {
+  typedef f16x8_t type;
+  static __device__ __forceinline__ f32x16_t mfma(type x, type y, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(x, y, c, 0, 0, 0);
+  }
+};
+
+// ---- LDS layout ------------------------------------------------------------------
+// A slab is rows x BK 16-bit values, i.e. rows x (BK/8) chunks of 16 bytes.
+// Chunk c of row r is stored at chunk slot  r*(BK/8) + (c ^ swz(r)):  the XOR
+// spreads the 32 rows a fragment read touches over all LDS banks.
+template <int BK> __device__ __forceinline__ int swz(int r);
+template <> __device__ __forceinline__ int swz<64>(int r) { return (r & 7) ^ ((r >> 3) & 3); }
+template <> __device__ __forceinline__ int swz<32>(int r) {
+  return ((r >> 1) & 3) ^ ((r >> 3) & 1);
+}
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_cvoid_t;
+
+__device__ __forceinline__ void wait_vmcnt_0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// ---- tile scheduling -------------------------------------------------------------
+// Workgroups are handed to the 8 XCDs round-robin; each XCD has its own L2.
+// Re-number so that each XCD works through one contiguous run of tile ids, and
+// walk the tile grid in groups of `group_m` tile rows so that concurrently
+// running workgroups share A row-panels and B column-panels in that L2.
+__device__ __forceinline__ void tile_coords(const MfmaArgs& p, int wg, int n_wg,
+                                            int& tm, int& tn) {
+  int id = wg;
+  if (p.xcd_remap) {
+    const int per = n_wg >> 3;                 // n_wg is a multiple of 8 when remap is on
+    id = (wg & 7) * per + (wg >> 3);
+  }
+  const int in_group = p.group_m * p.tiles_n;
+  const int g = id / in_group;
+  const int first_m = g * p.group_m;
+  const int rows = min(p.tiles_m - first_m, p.group_m);
+  const int rem = id - g * in_group;
+  tm = first_m + rem % rows;
+  tn = rem / rows;
+}
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+struct MfmaTile {
+  static constexpr int kThreads = 64 * WM * WN;
+  static constexpr int kWaves = WM * WN;
+  static constexpr int WTM = BM / WM, WTN = BN / WN;     // per-wave block
+  static constexpr int MT = WTM / 32, NT = WTN / 32;     // 32x32 MFMA tiles per wave
+  static constexpr int CPR = BK / 8;                     // 16-byte chunks per slab row
+  static constexpr int RPI = 64 / CPR;                   // slab rows one wave-wide load covers
+  static constexpr int A_LOADS = BM / RPI / kWaves;      // direct-to-LDS loads per lane, A slab
+  static constexpr int B_LOADS = BN / RPI / kWaves;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+  static constexpr int KK = BK / 16;                     // MFMA k-steps per slab
+  static_assert(BM % (RPI * kWaves) == 0 && BN % (RPI * kWaves) == 0, "slab rows must divide over waves");
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave block must be a multiple of 32x32");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+__global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
+  typedef MfmaTile<T, BM, BN, BK, WM, WN, NSTAGE> Cfg;
+  typedef typename Frag<T>::type frag_t;
+  constexpr int MT = Cfg::MT, NT = Cfg::NT, CPR = Cfg::CPR, RPI = Cfg::RPI;
+
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[Cfg::LDS_BYTES];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+
+  int tm, tn;
+  tile_coords(p, blockIdx.x, gridDim.x, tm, tn);
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int64_t batch = blockIdx.y;
+
+  const T* Ab = (const T*)p.A + batch * p.stride_a + (int64_t)row0 * p.lda;
+  const T* Bb = (const T*)p.B + batch * p.stride_b + (int64_t)col0 * p.ldb;
+
+  // ---- global -> LDS addressing -------------------------------------------------
+  // Load q of this wave fills LDS bytes [slab + (wave*LOADS + q)*1024, +1024): lane
+  // l writes 16 bytes at +16*l, i.e. slab row (wave*LOADS+q)*RPI + l/CPR, slot l%CPR,
+  // which must receive logical chunk  slot ^ swz(row).  Rows past the matrix edge
+  // are clamped to the last valid row (their results are never stored).
+  uint32_t a_off[Cfg::A_LOADS], b_off[Cfg::B_LOADS];
+#pragma unroll
+  for (int q = 0; q < Cfg::A_LOADS; ++q) {
+    const int r = (wave * Cfg::A_LOADS + q) * RPI + lane / CPR;
+    const int c = (lane % CPR) ^ swz<BK>(r);
+    const int rr = min(r, p.M - 1 - row0);
+    a_off[q] = (uint32_t)(((int64_t)rr * p.lda + c * 8) * 2);
+  }
+#pragma unroll
+  for (int q = 0; q < Cfg::B_LOADS; ++q) {
+    const int r = (wave * Cfg::B_LOADS + q) * RPI + lane / CPR;
+    const int c = (lane % CPR) ^ swz<BK>(r);
+    const int rr = min(r, p.N - 1 - col0);
+    b_off[q] = (uint32_t)(((int64_t)rr * p.ldb + c * 8) * 2);
+  }
+
+  auto issue_loads = [&](int kt, int stage) {
+    const char* ga = (const char*)Ab + (int64_t)kt * (BK * 2);
+    const char* gb = (const char*)Bb + (int64_t)kt * (BK * 2);
+    unsigned char* sa = smem + stage * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024);
+    unsigned char* sb = smem + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024);
+#pragma unroll
+    for (int q = 0; q < Cfg::A_LOADS; ++q)
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(ga + a_off[q]),
+                                       (lds_void_t*)(sa + q * 1024), 16, 0, 0);
+#pragma unroll
+    for (int q = 0; q < Cfg::B_LOADS; ++q)
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(gb + b_off[q]),
+                                       (lds_void_t*)(sb + q * 1024), 16, 0, 0);
+  };
+
+  // K tail: the last slab may hold fewer than BK valid columns.  Chunks past K
+  // must read as zero, which a direct-to-LDS load cannot do, so that one slab goes
+  // through registers.  (K is a multiple of 8: chunks are never split.)
+  auto issue_loads_tail = [&](int kt, int stage) {
+    const int kvalid = p.K - kt * BK;                      // valid columns in this slab
+    const char* ga = (const char*)Ab + (int64_t)kt * (BK * 2);
+    const char* gb = (const char*)Bb + (int64_t)kt * (BK * 2);
+    unsigned char* sa = smem + stage * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024);
+    unsigned char* sb = smem + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024);
+#pragma unroll
+    for (int q = 0; q < Cfg::A_LOADS; ++q) {
+      const int r = (wave * Cfg::A_LOADS + q) * RPI + lane / CPR;
+      const int c = (lane % CPR) ^ swz<BK>(r);
+      u32x4_t v = {0u, 0u, 0u, 0u};
+      if (c * 8 < kvalid) v = *(const u32x4_t*)(ga + a_off[q]);
+      *(u32x4_t*)(sa + q * 1024 + lane * 16) = v;
+    }
+#pragma unroll
+    for (int q = 0; q < Cfg::B_LOADS; ++q) {
+      const int r = (wave * Cfg::B_LOADS + q) * RPI + lane / CPR;
+      const int c = (lane % CPR) ^ swz<BK>(r);
+      u32x4_t v = {0u, 0u, 0u, 0u};
+      if (c * 8 < kvalid) v = *(const u32x4_t*)(gb + b_off[q]);
+      *(u32x4_t*)(sb + q * 1024 + lane * 16) = v;
+    }
+  };
+
+  // ---- LDS -> fragment addressing -------------------------------------------------
+  // MFMA 32x32x16 operand: lane l holds 8 consecutive k of row (l % 32), k-octet l / 32.
+  const int fr = lane & 31, fh = lane >> 5;
+  const int a_row = wm * Cfg::WTM + fr;
+  const int b_row = wn * Cfg::WTN + fr;
+  // byte offset of (row, chunk kk*2+fh) = row*BK*2 + (((kk*2+fh) ^ swz(row)) * 16)
+  uint32_t a_rd[Cfg::KK], b_rd[Cfg::KK];
+#pragma unroll
+  for (int kk = 0; kk < Cfg::KK; ++kk) {
+    a_rd[kk] = a_row * (BK * 2) + (((kk * 2 + fh) ^ swz<BK>(a_row)) * 16);
+    b_rd[kk] = Cfg::A_BYTES + b_row * (BK * 2) + (((kk * 2 + fh) ^ swz<BK>(b_row)) * 16);
+  }
+
+  f32x16_t acc[MT][NT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.0f;
+
+  // Fragment registers, double-buffered over the MFMA k-steps of a slab: while the
+  // MFMAs of step kk run, the LDS reads of step kk+1 are already in flight.
+  frag_t af[2][MT], bf[2][NT];
+
+  auto read_frags = [&](int stage, int kk, int buf) {
+    const unsigned char* s = smem + stage * Cfg::STAGE_BYTES;
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      af[buf][m] = *(const frag_t*)(s + a_rd[kk] + m * (32 * BK * 2));
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+      bf[buf][n] = *(const frag_t*)(s + b_rd[kk] + n * (32 * BK * 2));
+  };
+  // Operands swapped (B fragment first) so that each lane ends up holding one row
+  // of C and runs of 4 consecutive columns: that is what the stores want.
+  auto mfma_step = [&](int buf) {
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+        acc[m][n] = Frag<T>::mfma(bf[buf][n], af[buf][m], acc[m][n]);
+  };
+  // The wave issues in order and runs alone on its SIMD, so every wait it hits is
+  // MFMA time lost.  Pin the instruction order: the LDS reads of the next step go
+  // out one per MFMA at the start of the current step, which leaves the rest of the
+  // step's MFMAs to cover their latency; at a hand-over the reads of the new slab
+  // go first and the global loads that refill the freed stage follow, two per MFMA.
+  auto interleave = [&]() {
+    constexpr int kReads = MT + NT, kMfma = MT * NT;
+#pragma unroll
+    for (int i = 0; i < kReads; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+    }
+    if (kMfma > kReads) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
+  };
+  auto interleave_hand_over = [&]() {
+    constexpr int kReads = MT + NT, kMfma = MT * NT;
+    constexpr int kLoads = Cfg::A_LOADS + Cfg::B_LOADS;
+#pragma unroll
+    for (int i = 0; i < kReads; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+    }
+    constexpr int kLeft = kMfma > kReads ? kMfma - kReads : 1;
+    constexpr int per = (kLoads + kLeft - 1) / kLeft;
+#pragma unroll
+    for (int i = 0; i < kLeft; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x020, per, 0); // global -> LDS loads
+    }
+  };
+
+  // ---- main loop ------------------------------------------------------------------
+  // Slab t lives in LDS stage t % NSTAGE.  The hand-over to slab t+1 happens before
+  // the last MFMA step of slab t (whose fragments are already in registers), so
+  // the barrier and the first fragment reads of slab t+1 hide behind those MFMAs,
+  // and stage t % NSTAGE is refilled with slab t+NSTAGE right after the barrier.
+  const int T_full = p.K / BK;                 // slabs loaded direct-to-LDS
+  const int T_all = (p.K + BK - 1) / BK;       // + possibly one tail slab
+  constexpr int kLoadsPerSlab = Cfg::A_LOADS + Cfg::B_LOADS;
+  constexpr int D = NSTAGE;                    // prefetch distance in slabs
+  constexpr int KK = Cfg::KK;
+  static_assert(KK % 2 == 0, "fragment double buffer assumes an even number of k-steps");
+
+  // Own LDS reads retired (the stage may be refilled) and own loads of the wanted
+  // slab landed, the loads of `kLater` later slabs may stay in flight; then all
+  // waves meet.
+  auto hand_over = [&](auto later) {
+    constexpr int kLater = decltype(later)::value;
+    __builtin_amdgcn_sched_barrier(0);         // nothing is scheduled across this point
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLater * kLoadsPerSlab) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  typedef std::integral_constant<int, 0> none_later;
+
+#pragma unroll
+  for (int s = 0; s < D; ++s) {
+    if (s < T_full) issue_loads(s, s);
+    else if (s < T_all) issue_loads_tail(s, s);
+  }
+  if (D <= T_full) hand_over(std::integral_constant<int, D - 1>());
+  else hand_over(none_later());
+  read_frags(0, 0, 0);
+
+  // steady state: slab t+D exists and is a full slab
+  int t = 0;
+  for (; t + D < T_full; ++t) {
+    const int stage = t % NSTAGE;
+#pragma unroll
+    for (int kk = 0; kk < KK - 1; ++kk) {
+      read_frags(stage, kk + 1, (kk + 1) & 1);
+      mfma_step(kk & 1);
+      interleave();
+    }
+    hand_over(std::integral_constant<int, (D >= 2 ? D - 2 : 0)>());
+    read_frags((t + 1) % NSTAGE, 0, 0);
+    issue_loads(t + D, (t + D) % NSTAGE);
+    mfma_step((KK - 1) & 1);
+    interleave_hand_over();
+  }
+  // drain: the remaining (at most D, plus a tail) slabs
+  for (; t < T_all; ++t) {
+    const int stage = t % NSTAGE;
+#pragma unroll
+    for (int kk = 0; kk < KK - 1; ++kk) {
+      read_frags(stage, kk + 1, (kk + 1) & 1);
+      mfma_step(kk & 1);
+      interleave();
+    }
+    if (t + 1 < T_all) {
+      hand_over(none_later());
+      if (t + D < T_all) issue_loads_tail(t + D, (t + D) % NSTAGE);   // only a tail slab can be left
+      read_frags((t + 1) % NSTAGE, 0, 0);
+    }
+    mfma_step((KK - 1) & 1);
+  }
+
+  // ---- epilogue ---------------------------------------------------------------------
+  // Lane l of a 32x32 accumulator tile holds row (l % 32) and, in register r,
+  // column 8*(r/4) + 4*(l/32) + r%4.
+  const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
+  const int act = p.act;
+  const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C & 15) == 0) && (p.stride_c % 4 == 0);
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const int i = row0 + wm * Cfg::WTM + m * 32 + fr;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int j = col0 + wn * Cfg::WTN + n * 32 + g * 8 + fh * 4;
+        if (i >= p.M || j >= p.N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[m][n][g * 4 + e];
+        const bool full = (j + 3 < p.N);
+        if (bias) {
+          if (full) {
+            const f32x4_t bv = *(const f32x4_t*)(bias + j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += bv[e];
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (j + e < p.N) v[e] += bias[j + e];
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = apply_activation(act, v[e]);
+        const int64_t o = batch * p.stride_c + (int64_t)i * p.ldc + j;
+        if (p.c_f32) {
+          float* c = (float*)p.C + o;
+          if (full && vec_ok) {
+            f32x4_t w = {v[0], v[1], v[2], v[3]};
+            *(f32x4_t*)c = w;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (j + e < p.N) c[e] = v[e];
+          }
+        } else {
+          T* c = (T*)p.C + o;
+          if (full && vec_ok) {
+            u32x2_t w = {pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3])};
+            *(u32x2_t*)c = w;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (j + e < p.N) c[e] = from_float<T>(v[e]);
+          }
+        }
+      }
+    }
+  }
+}
+
+}  // namespace mi355gemm

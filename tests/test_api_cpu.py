@@ -1,0 +1,126 @@
+"""Host-side behaviour of the C ABI that needs no GPU: the library loads, exports
+what include/gemm.h declares, validates descriptors and picks kernels."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2603_12440_amd as g
+    if not os.path.exists(g.library_path()):
+        from paper_2603_12440_amd.build import build_library
+        build_library()
+    g.load_library()
+    return g
+
+
+def test_every_declared_symbol_is_exported(g):
+    header = open(os.path.join(ROOT, "include", "gemm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(gemm_[a-z_]+)\s*\(", header))
+    assert {"gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
+            "gemm_create_config", "gemm_config_count", "gemm_config_name"} <= names
+    lib = ctypes.CDLL(g.library_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_exposes_the_same_names(g):
+    for n in ("gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
+              "gemm_create_config", "gemm_config_count", "gemm_config_name"):
+        assert callable(getattr(g, n))
+
+
+def _status(g, **kw):
+    try:
+        p = g.gemm_create(g.GemmDesc(**kw))
+    except g.GemmError as e:
+        return e.status
+    g.gemm_destroy(p)
+    return 0
+
+
+def test_descriptor_validation(g):
+    ok = dict(M=64, N=64, K=64)
+    assert _status(g, **ok) == 0
+    assert _status(g, M=0, N=64, K=64) == -2
+    assert _status(g, M=64, N=-1, K=64) == -2
+    assert _status(g, M=64, N=64, K=0) == -2
+    assert _status(g, **ok, batch=0) == -2
+    assert _status(g, **ok, lda=63) == -3            # row-major A needs lda >= K
+    assert _status(g, **ok, ldb=10) == -3
+    assert _status(g, **ok, ldc=1) == -3
+    assert _status(g, **ok, batch=2, stride_c=10) == -3   # overlapping output batches
+    assert _status(g, **ok, batch=2, stride_bias=3, epilogue=g.EPI_BIAS) == -3
+    assert _status(g, **ok, dtype=g.BF16, dtype_b=g.F16) == -4
+    assert _status(g, **ok, dtype=g.F32, dtype_c=g.BF16) == -4
+    assert _status(g, **ok, dtype_bias=g.BF16) == -4
+    assert _status(g, **ok, epilogue=7) == -8
+    assert _status(g, **ok, layout_a=2) == -8
+    assert _status(g, **ok, dtype=3) == -8
+    assert _status(g, M=1 << 31, N=64, K=64) == -2
+
+
+def test_null_handling(g):
+    lib = g.load_library()
+    out = ctypes.c_void_p(123)
+    assert lib.gemm_create(None, ctypes.byref(out)) == -1 and not out.value
+    assert lib.gemm_create(ctypes.byref(g.GemmDesc(8, 8, 8)), None) == -1
+    assert lib.gemm_destroy(None) == 0
+    assert lib.gemm_run(None, 16, 16, 16, None, None) == -1
+    assert lib.gemm_plan_info(None, None, 0) == -1
+    p = g.gemm_create(g.GemmDesc(64, 64, 64))
+    assert lib.gemm_run(p.handle, None, 16, 16, None, None) == -1
+    assert lib.gemm_run(p.handle, 16, 16, 16, 16, None) == -1     # bias given, epilogue has none
+    assert lib.gemm_run(p.handle, 16, 24, 32, None, None) == -5   # MFMA path wants 16-byte alignment
+    g.gemm_destroy(p)
+    q = g.gemm_create(g.GemmDesc(64, 64, 64, epilogue=g.EPI_BIAS))
+    assert lib.gemm_run(q.handle, 16, 16, 16, None, None) == -1   # bias missing
+    g.gemm_destroy(q)
+    for s in range(-9, 1):
+        assert g.gemm_status_string(s) not in ("", "unknown status")
+    assert g.gemm_status_string(-99) == "unknown status"
+
+
+def test_kernel_choice(g):
+    def kernel(**kw):
+        p = g.gemm_create(g.GemmDesc(**kw))
+        info = p.info()
+        g.gemm_destroy(p)
+        return info
+    assert "kernel=mfma_256x256" in kernel(M=8192, N=8192, K=8192)
+    assert "grid=1024,1,1" in kernel(M=8192, N=8192, K=8192)
+    for m in (1, 4, 16):
+        assert "kernel=skinny" in kernel(M=m, N=8192, K=8192)
+    assert "kernel=simt" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    # 16-bit operands the tiled kernels cannot take go to the general kernel
+    assert "kernel=simt" in kernel(M=256, N=256, K=256, layout_a=g.COL_MAJOR)
+    assert "kernel=simt" in kernel(M=256, N=256, K=100)            # K not a multiple of 8
+    assert "kernel=simt" in kernel(M=256, N=256, K=256, lda=257)   # rows not 16-byte aligned
+    assert "kernel=mfma" in kernel(M=512, N=512, K=128, batch=64)
+    assert "kernel=mfma" in kernel(M=17, N=64, K=64)
+
+
+def test_config_table(g):
+    names = g.config_names()
+    assert len(names) == g.gemm_config_count() and len(set(names)) == len(names)
+    assert g.gemm_config_name(-1) is None and g.gemm_config_name(len(names)) is None
+    d = g.GemmDesc(256, 256, 256, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    for i, n in enumerate(names):
+        try:
+            p = g.gemm_create_config(d, i)
+        except g.GemmError as e:
+            assert e.status == -9 and not n.startswith("simt")     # fp32 only runs on the general kernel
+        else:
+            assert n.startswith("simt") and n in p.info()
+            g.gemm_destroy(p)
+    with pytest.raises(g.GemmError):
+        g.gemm_create_config(d, len(names))
+    d16 = g.GemmDesc(32, 4096, 4096)
+    with pytest.raises(g.GemmError):                                # skinny kernels stop at M = 16
+        g.gemm_create_config(d16, names.index("skinny_m16_r1_w4"))

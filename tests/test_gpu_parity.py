@@ -1,0 +1,279 @@
+"""Parity of the HIP kernels (through the C ABI) against the CPU oracle, element
+by element on seeded inputs.  Integer-valued inputs must match bit for bit;
+random inputs must satisfy the stated tolerance (E1), the a-priori fp32 error
+bound (E2) and the paper's relative criterion (E3); see tests/helpers.py."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from helpers import assert_parity, compare, gpu_desc, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2603_12440_amd as g
+    g.load_library()          # raises if the HIP library is missing: no fallback
+    assert torch.cuda.is_available()
+    return g
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cfg_index(g, name):
+    return g.config_names().index(name)
+
+
+def mfma_configs(g):
+    return [n for n in g.config_names() if n.startswith("mfma")]
+
+
+def skinny_config_for(g, m):
+    for n in g.config_names():
+        if n.startswith("skinny_m") and int(n.split("_")[1][1:]) >= m:
+            return n
+    raise AssertionError(m)
+
+
+# ---- exact cases: small integers, every kernel family ---------------------------------
+
+def exact_case(g, o, w, config, out_dtype=None, lo=-1, hi=1, **pads):
+    sa, sb = wl.operand_shapes(w)
+    A = wl.small_integers(sa, w.seed_a, lo, hi, w.dtype)
+    B = wl.small_integers(sb, w.seed_b, lo, hi, w.dtype)
+    bias = wl.small_integers((w.N,), w.seed_bias, -3, 3, "f32") if w.has_bias else None
+    say(f"exact {w.M}x{w.N}x{w.K} b{w.batch} {w.dtype} {w.epilogue} cfg={config} {pads}")
+    C = run_gpu(g, w, A, B, bias, config=cfg_index(g, config) if config else -1,
+                out_dtype=out_dtype, **pads)
+    ref = run_oracle(o, w, A, B, bias, want=("y",))
+    assert np.array_equal(wl.to_float64(C), ref["y"]), config
+
+
+@pytest.mark.parametrize("shape", [(256, 256, 64), (300, 520, 200), (33, 47, 8), (512, 384, 72),
+                                   (257, 255, 136), (64, 1000, 1024)])
+def test_mfma_exact_small_integers(g, oracle, shape):
+    """Multiple tiles, ragged M and N edges, K tails (K % 64 != 0), all tile shapes."""
+    M, N, K = shape
+    for cfg in mfma_configs(g):
+        w = wl.Workload("t", M, N, K, seed_a=M + 1, seed_b=N + 2)
+        exact_case(g, oracle, w, cfg)
+        exact_case(g, oracle, w, cfg, out_dtype="f32", lo=-2, hi=2)
+
+
+def test_mfma_exact_padded_and_fp16(g, oracle):
+    for cfg in mfma_configs(g):
+        w = wl.Workload("t", 200, 264, 328, seed_a=5, seed_b=6)
+        exact_case(g, oracle, w, cfg, pad_a=8, pad_b=16, pad_c=3)
+        exact_case(g, oracle, wl.scaled(w, dtype="f16"), cfg, pad_a=16, pad_b=8, pad_c=4)
+        exact_case(g, oracle, wl.scaled(w, epilogue="bias_relu", seed_bias=9), cfg, out_dtype="f32", pad_c=5)
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 13, 16])
+def test_skinny_exact_small_integers(g, oracle, M):
+    cfg = skinny_config_for(g, M)
+    for (N, K) in [(1000, 520), (64, 8), (4099, 1024), (8, 4096)]:
+        w = wl.Workload("t", M, N, K, seed_a=M, seed_b=N)
+        exact_case(g, oracle, w, cfg, out_dtype="f32")
+    w = wl.Workload("t", M, 515, 136, seed_a=7, seed_b=8)
+    exact_case(g, oracle, w, cfg, pad_a=8, pad_b=8, pad_c=1)
+    exact_case(g, oracle, wl.scaled(w, dtype="f16", epilogue="bias_relu", seed_bias=3), cfg, out_dtype="f32")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("la,lb,lc", [("row", "row", "row"), ("row", "col", "row"), ("col", "row", "col"),
+                                      ("col", "col", "row"), ("row", "row", "col")])
+def test_general_kernel_exact_all_layouts(g, oracle, dtype, la, lb, lc):
+    for cfg in ("simt_64x64x16", "simt_32x32x16"):
+        w = wl.Workload("t", 70, 130, 45, dtype=dtype, layout_a=la, layout_b=lb, seed_a=3, seed_b=4)
+        exact_case(g, oracle, w, cfg, layout_c=lc, pad_a=1, pad_b=2, pad_c=3)
+    w = wl.Workload("t", 65, 33, 19, dtype=dtype, layout_a=la, layout_b=lb, batch=3,
+                    epilogue="bias", seed_a=5, seed_b=6, seed_bias=7)
+    exact_case(g, oracle, w, None, layout_c=lc, out_dtype="f32")
+
+
+# ---- closed forms on the GPU --------------------------------------------------------------
+
+@pytest.mark.parametrize("K", [128, 256, 4096, 8192, 14336])
+def test_all_ones_gives_K(g, K):
+    """Every k contributes exactly once (K and all partial sums are exact in fp32,
+    and these K are exact in bf16)."""
+    for (M, N, cfg) in [(256, 256, "mfma_256x256x64_w2x2_s2"), (256, 256, "mfma_256x256x32_w2x2_s4"),
+                        (130, 70, "mfma_128x128x64_w2x2_s2"), (1, 96, "skinny_m1_r4_w4"),
+                        (16, 33, "skinny_m16_r1_w4")]:
+        w = wl.Workload("t", M, N, K)
+        say(f"all-ones {M}x{N}x{K} {cfg}")
+        A = torch.ones((1, M, K), dtype=torch.bfloat16)
+        B = torch.ones((1, N, K), dtype=torch.bfloat16)
+        C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg))
+        assert torch.all(C.float() == float(K)), cfg
+
+
+def test_one_hot_k_sweep_copies_columns_of_b(g):
+    """A[i, k0] = 1 only: C[i, :] = B[k0, :] exactly.  k0 sweeps slab and MFMA-step
+    boundaries, so a dropped, duplicated or shifted k-slab cannot hide."""
+    K = 328
+    ks = [0, 1, 7, 8, 15, 16, 31, 32, 63, 64, 65, 127, 128, 191, 192, 255, 256, 319, 320, 327]
+    for cfg, M, N in [(c, 300, 260) for c in mfma_configs(g)] + [("skinny_m4_r4_w4", 4, 260),
+                                                                ("skinny_m16_r1_w4", 16, 70)]:
+        w = wl.Workload("t", M, N, K, seed_b=77)
+        say(f"one-hot {cfg}")
+        A = wl.one_hot_columns(M, K, ks).unsqueeze(0)
+        _, B, _ = wl.make_inputs(w)
+        C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg))
+        for i in range(M):
+            assert torch.equal(C[0, i], B[0, :, ks[i % len(ks)]]), (cfg, i)
+
+
+def test_identity(g):
+    n = 512
+    w = wl.Workload("t", n, n, n, seed_a=1, seed_b=2)
+    A, B, _ = wl.make_inputs(w)
+    eye = torch.eye(n, dtype=torch.bfloat16).unsqueeze(0)
+    for cfg in mfma_configs(g):
+        say(f"identity {cfg}")
+        assert torch.equal(run_gpu(g, w, eye, B, None, config=cfg_index(g, cfg))[0], B[0].T)
+        assert torch.equal(run_gpu(g, w, A, eye, None, config=cfg_index(g, cfg))[0], A[0])
+
+
+def test_bias_only_and_applied_once(g):
+    """A = 0: C = round(act(bias[j])) per column; all-ones: K + bias."""
+    M, N, K = 260, 300, 64
+    bias = wl._draw(("uniform", 3.0), (N,), 5)
+    for cfg in ["mfma_256x256x64_w2x2_s2", "simt_64x64x16"]:
+        w = wl.Workload("t", M, N, K, epilogue="bias")
+        C = run_gpu(g, w, torch.zeros((1, M, K), dtype=torch.bfloat16),
+                    torch.ones((1, N, K), dtype=torch.bfloat16), bias, config=cfg_index(g, cfg))
+        assert torch.equal(C[0], bias.to(torch.bfloat16).expand(M, N)), cfg
+        C = run_gpu(g, w, torch.ones((1, M, K), dtype=torch.bfloat16),
+                    torch.ones((1, N, K), dtype=torch.bfloat16), bias, config=cfg_index(g, cfg), out_dtype="f32")
+        assert torch.equal(C[0], (bias + float(K)).expand(M, N)), cfg
+    w = wl.Workload("t", 3, N, K, epilogue="bias_relu")
+    C = run_gpu(g, w, torch.zeros((1, 3, K), dtype=torch.bfloat16),
+                torch.ones((1, N, K), dtype=torch.bfloat16), bias, out_dtype="f32")
+    assert torch.equal(C[0], bias.clamp(min=0).expand(3, N))
+
+
+# ---- random data against the oracle -----------------------------------------------------------
+
+RANDOM_CASES = [
+    # scaled-down versions of the benchmark workloads (same distributions and layouts)
+    ("square_8192", dict(M=512, N=768, K=1024)),
+    ("llm_4096x14336x4096", dict(M=384, N=896, K=512)),
+    ("llm_4096x4096x14336", dict(M=256, N=256, K=3584)),
+    ("llm_4096x6144x4096", dict(M=300, N=200, K=520)),
+    ("gelu_8192x16384x4096", dict(M=512, N=1024, K=512)),
+    ("gelu_8192x16384x4096", dict(M=250, N=1030, K=264)),
+    ("batched_64x512x512x128", dict(batch=5)),
+]
+
+
+@pytest.mark.parametrize("name,changes", RANDOM_CASES)
+def test_mfma_random_against_oracle(g, oracle, name, changes):
+    w = wl.scaled(wl.WORKLOADS[name], **changes)
+    A, B, bias = wl.make_inputs(w)
+    ref = run_oracle(oracle, w, A, B, bias)
+    for cfg in [None] + mfma_configs(g):
+        say(f"random {name} {changes} cfg={cfg}")
+        C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg) if cfg else -1)
+        r = assert_parity(w, C, ref, A, B, bias)
+        say("   ", r)
+
+
+@pytest.mark.parametrize("epilogue", ["none", "bias", "bias_relu", "bias_gelu_erf", "bias_gelu_tanh", "relu", "gelu_erf"])
+def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
+    for (M, N, K, cfg) in [(260, 264, 136, "mfma_256x256x64_w2x2_s2"), (130, 140, 72, "mfma_128x128x64_w2x2_s2"),
+                           (3, 515, 264, "skinny_m4_r4_w4"), (16, 100, 1032, "skinny_m16_r1_w4"),
+                           (70, 90, 50, "simt_64x64x16")]:
+        # pre-activations of order 1 so that the activations' curved parts are exercised
+        w = wl.Workload("t", M, N, K, dist_a=("normal", 1.0), dist_b=("normal", 1.5 / np.sqrt(K)),
+                        epilogue=epilogue, dist_bias=("uniform", 1.0), seed_a=11, seed_b=12, seed_bias=13)
+        A, B, bias = wl.make_inputs(w)
+        ref = run_oracle(oracle, w, A, B, bias)
+        for od in (None, "f32"):
+            say(f"epilogue {epilogue} {cfg} out={od}")
+            C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg), out_dtype=od)
+            assert_parity(w, C, ref, A, B, bias, out_dtype=od)
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_skinny_random_against_oracle(g, oracle, M):
+    for N, K in [(1024, 8192), (3000, 1032)]:
+        w = wl.scaled(wl.WORKLOADS[f"skinny_m{M}_n8192"], N=N, K=K)
+        A, B, bias = wl.make_inputs(w)
+        ref = run_oracle(oracle, w, A, B, bias)
+        say(f"skinny random M={M} N={N} K={K}")
+        C, info = run_gpu(g, w, A, B, bias, return_plan_info=True)
+        assert "kernel=skinny" in info
+        assert_parity(w, C, ref, A, B, bias)
+        # the matrix-core path must agree with it on the same data
+        C2 = run_gpu(g, w, A, B, bias, config=cfg_index(g, "mfma_128x128x64_w2x2_s2"))
+        assert_parity(w, C2, ref, A, B, bias)
+
+
+def test_fp32_config_full_size(g, oracle):
+    """The 256^3 fp32 case at full size: true fp32 arithmetic (tolerance 1e-6 forbids
+    any narrowing of the operands)."""
+    w = wl.WORKLOADS["f32_256"]
+    A, B, _ = wl.make_inputs(w)
+    ref = run_oracle(oracle, w, A, B, None)
+    for cfg in (None, "simt_64x64x16", "simt_32x32x16"):
+        say(f"f32_256 cfg={cfg}")
+        C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg) if cfg else -1)
+        r = assert_parity(w, C, ref, A, B, None)
+        assert r["e1"] < 1e-7
+    # transpose invariance on the GPU: C^T = B^T A^T through swapped operands and layouts
+    wt = wl.scaled(w, layout_a="col", layout_b="col")
+    Ct = run_gpu(g, wt, B, A, None)     # B (K x N row-major) read as B^T column-major; same for A
+    ref_t = {k: v.transpose(0, 2, 1) for k, v in ref.items()}
+    assert_parity(wt, Ct, ref_t, A, B, None)
+
+
+def test_fp16_random(g, oracle):
+    w = wl.Workload("t", 300, 260, 520, dtype="f16", dist_a=("uniform", 1.0),
+                    dist_b=("uniform", 1.0 / np.sqrt(520)), seed_a=21, seed_b=22)
+    A, B, _ = wl.make_inputs(w)
+    ref = run_oracle(oracle, w, A, B, None)
+    for cfg in [None] + mfma_configs(g) + ["simt_64x64x16"]:
+        say(f"fp16 cfg={cfg}")
+        C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg) if cfg else -1)
+        assert_parity(w, C, ref, A, B, None)
+
+
+def test_batches_and_bias_strides(g, oracle):
+    """Each batch reads its own slab; shared bias (stride 0) against one per batch."""
+    for cfg in ("mfma_128x128x64_w2x2_s2", "simt_64x64x16", "skinny_m4_r4_w4"):
+        M = 4 if cfg.startswith("skinny") else 96
+        w = wl.Workload("t", M, 136, 72, batch=4, epilogue="bias_gelu_erf", seed_a=31, seed_b=32)
+        A, B, _ = wl.make_inputs(w)
+        bias = wl._draw(("uniform", 1.0), (4 * 136,), 33)
+        for sb in (0, 136):
+            say(f"batched {cfg} stride_bias={sb}")
+            C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg), stride_bias=sb)
+            ref = run_oracle(oracle, w, A, B, bias, stride_bias=sb)
+            assert_parity(w, C, ref, A, B, bias)
+    # constant per batch: C_b = K (b+1)^2
+    w = wl.Workload("t", 64, 64, 64, batch=3)
+    A = torch.stack([torch.full((64, 64), float(b + 1)) for b in range(3)]).to(torch.bfloat16)
+    C = run_gpu(g, w, A, A.clone(), None, out_dtype="f32")
+    for b in range(3):
+        assert torch.all(C[b] == 64.0 * (b + 1) ** 2)
+
+
+def test_misaligned_pointer_is_refused(g):
+    w = wl.Workload("t", 64, 64, 64)
+    dev = torch.device("cuda:0")
+    buf = torch.zeros(64 * 64 + 8, dtype=torch.bfloat16, device=dev)
+    C = torch.zeros(64 * 64, dtype=torch.bfloat16, device=dev)
+    plan = g.gemm_create(gpu_desc(g, w))
+    with pytest.raises(g.GemmError) as e:
+        g.gemm_run(plan, buf[1:], buf, C)          # 2-byte aligned A on the 16-byte path
+    assert e.value.status == -5
+    g.gemm_run(plan, buf, buf, C)
+    torch.cuda.synchronize()
+    g.gemm_destroy(plan)
