@@ -78,7 +78,7 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
     pb, pi, pj = wl.sample_points(w, 2048, 99)
     ref = oracle.ref_gemm_points(oracle_problem(oracle, w), a, b, bz, pb, pi, pj, want=("y", "t", "s"))
     got = gpu_out.to(torch.float64).numpy()[pb, pi, pj]
-    u_out = {"bf16": 2.0 ** -9, "f16": 2.0 ** -11, "f32": 2.0 ** -24}[w.dtype]
+    u_out = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24}[w.dtype]
     acc = 1.13 * w.K * 2.0 ** -24 * ref["s"] + 16 * 2.0 ** -24 * (np.abs(ref["t"]) + 1.0)
     bound = acc + u_out * (np.abs(ref["y"]) + acc) * 1.001 + 1e-30
     matches = bool(np.all(np.abs(got - ref["y"]) <= bound))

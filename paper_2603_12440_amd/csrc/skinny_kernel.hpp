@@ -3,7 +3,8 @@
 // The weight matrix W (N x K, K contiguous) is read exactly once from HBM and
 // nothing else matters: each wavefront owns RPW rows of W at a time, every lane
 // streams 16-byte pieces of those rows, multiplies them with the matching
-// pieces of the (tiny, cache-resident) x rows in fp32 on the vector ALUs, and
+// pieces of the (tiny, cache-resident) x rows with packed dot products (fp32
+// accumulate) on the vector ALUs, and
 // the 64 partial sums are combined with DPP lane rotations.  No matrix cores,
 // no workgroup barriers.  Paper taxonomy (Sec. 3.2): d_mem = 1 (coalesced,
 // vectorised loads), d_sync = 2 (sub-group reductions).
@@ -39,22 +40,27 @@ __device__ __forceinline__ float wave_sum(float v) {
   return s;
 }
 
-// 8 packed 16-bit values (one 16-byte piece) -> 8 floats.
-template <typename T> __device__ __forceinline__ void unpack8(const u32x4_t& u, float* f);
-template <> __device__ __forceinline__ void unpack8<bf16_t>(const u32x4_t& u, float* f) {
+// acc + dot product of two 16-byte pieces (8 packed 16-bit values each), with the
+// packed dot-product instructions (v_dot2c_f32_bf16 / v_dot2c_f32_f16): products
+// of two 16-bit values are exact in fp32, the sums are rounded in fp32.
+template <typename T> __device__ __forceinline__ float dot8(const u32x4_t& x, const u32x4_t& w, float acc);
+template <> __device__ __forceinline__ float dot8<bf16_t>(const u32x4_t& x, const u32x4_t& w, float acc) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    f[2 * i] = __builtin_bit_cast(float, u[i] << 16);
-    f[2 * i + 1] = __builtin_bit_cast(float, u[i] & 0xffff0000u);
+    const uint32_t xi = x[i], wi = w[i];   // scalars first: bit_cast of a vector element lvalue is unreliable
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xi),
+                                          __builtin_bit_cast(bf16x2_t, wi), acc, false);
   }
+  return acc;
 }
-template <> __device__ __forceinline__ void unpack8<f16_t>(const u32x4_t& u, float* f) {
+template <> __device__ __forceinline__ float dot8<f16_t>(const u32x4_t& x, const u32x4_t& w, float acc) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    f16x2_t h = __builtin_bit_cast(f16x2_t, u[i]);
-    f[2 * i] = (float)h[0];
-    f[2 * i + 1] = (float)h[1];
+    const uint32_t xi = x[i], wi = w[i];
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, xi),
+                                 __builtin_bit_cast(f16x2_t, wi), acc, false);
   }
+  return acc;
 }
 
 // MB = number of x rows handled (M rounded up; rows past M are clamped for the
@@ -94,18 +100,11 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
 #pragma unroll
       for (int r = 0; r < RPW; ++r)
         wv[r] = __builtin_nontemporal_load((const u32x4_t*)(wrow[r] + k));
-      float wf[RPW][8];
-#pragma unroll
-      for (int r = 0; r < RPW; ++r) unpack8<T>(wv[r], wf[r]);
 #pragma unroll
       for (int m = 0; m < MB; ++m) {
         const u32x4_t xv = *(const u32x4_t*)(xrow[m] + k);
-        float xf[8];
-        unpack8<T>(xv, xf);
 #pragma unroll
-        for (int r = 0; r < RPW; ++r)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[m][r] = fmaf(xf[e], wf[r][e], acc[m][r]);
+        for (int r = 0; r < RPW; ++r) acc[m][r] = dot8<T>(xv, wv[r], acc[m][r]);
       }
     }
 

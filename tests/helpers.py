@@ -16,7 +16,7 @@ import torch
 import workloads as wl
 
 U32 = 2.0 ** -24
-OUT_ROUNDOFF = {"bf16": 2.0 ** -9, "f16": 2.0 ** -11, "f32": 2.0 ** -24}
+OUT_ROUNDOFF = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24}
 E1_TOL = {"bf16": 2e-3, "f16": 2e-3, "f32": 1e-6}
 
 
