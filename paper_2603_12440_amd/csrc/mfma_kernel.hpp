@@ -32,16 +32,20 @@ struct MfmaArgs {
 
 // ---- MFMA wrappers -----------------------------------------------------------
 template <typename T> struct Frag;
+// Issued through inline assembly: the accumulators are pinned to the AccVGPR file
+// ("+a") and, being volatile, the MFMAs keep their program order relative to each
+// other and to the (volatile) fragment reads, which is what the hand-made
+// software pipeline below relies on.
 template <> struct Frag<bf16_t> {
   typedef bf16x8_t type;
-  static __device__ __forceinline__ f32x16_t mfma(type x, type y, f32x16_t c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, c, 0, 0, 0);
+  static __device__ __forceinline__ void mfma(const type& x, const type& y, f32x16_t& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(x), "v"(y));
   }
 };
 template <> struct Frag<f16_t> {
   typedef f16x8_t type;
-  static __device__ __forceinline__ f32x16_t mfma(type x, type y, f32x16_t c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(x, y, c, 0, 0, 0);
+  static __device__ __forceinline__ void mfma(const type& x, const type& y, f32x16_t& c) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(x), "v"(y));
   }
 };
 
@@ -56,6 +60,32 @@ template <> __device__ __forceinline__ int swz<32>(int r) {
 }
 
 typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(3))) unsigned char lds_uchar_t;
+
+// 16-byte LDS read, asynchronous: the destination is valid only after a matching
+// s_waitcnt lgkmcnt.  Issued through volatile inline assembly so that reads and
+// MFMAs keep exactly their program order; the waits are placed by hand (the
+// compiler does not track these reads).
+template <typename F>
+__device__ __forceinline__ void lds_read_b128(F& dst, uint32_t addr, int offset) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(offset) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_lgkmcnt() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+// `n` is a constant after unrolling; the switch turns it into an immediate.
+__device__ __forceinline__ void wait_lgkmcnt_dyn(int n) {
+  switch (n) {
+    case 0: wait_lgkmcnt<0>(); break;   case 1: wait_lgkmcnt<1>(); break;
+    case 2: wait_lgkmcnt<2>(); break;   case 3: wait_lgkmcnt<3>(); break;
+    case 4: wait_lgkmcnt<4>(); break;   case 5: wait_lgkmcnt<5>(); break;
+    case 6: wait_lgkmcnt<6>(); break;   case 7: wait_lgkmcnt<7>(); break;
+    case 8: wait_lgkmcnt<8>(); break;   case 9: wait_lgkmcnt<9>(); break;
+    case 10: wait_lgkmcnt<10>(); break; case 11: wait_lgkmcnt<11>(); break;
+    case 12: wait_lgkmcnt<12>(); break; case 13: wait_lgkmcnt<13>(); break;
+    case 14: wait_lgkmcnt<14>(); break; default: wait_lgkmcnt<15>(); break;
+  }
+}
 typedef __attribute__((address_space(1))) const void global_cvoid_t;
 
 __device__ __forceinline__ void wait_vmcnt_0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -84,6 +114,51 @@ __device__ __forceinline__ void tile_coords(const MfmaArgs& p, int wg, int n_wg,
   tn = rem / rows;
 }
 
+// ---- instruction order of one MFMA k-step -----------------------------------------
+// A wave block of MT x NT MFMA tiles needs MT A-fragments and NT B-fragments per
+// k-step.  Reads are requested in the order a0 b0 b1 a1 b2 a2 ...; the MFMAs run in
+// the order in which both of their operands have been requested.
+template <int MT, int NT>
+struct StepOrder {
+  static constexpr int kReads = MT + NT, kMfma = MT * NT;
+  struct Tables {
+    int r_isb[kReads], r_idx[kReads];
+    int mm[kMfma], nn[kMfma];
+    int need[kMfma];        // request position of the later of MFMA i's two operands
+  };
+  static constexpr Tables make() {
+    Tables t{};
+    int pos_a[MT] = {}, pos_b[NT] = {};
+    int c = 0;
+    for (int i = 0; i < (MT > NT ? MT : NT); ++i) {
+      if (i == 0) {
+        t.r_isb[c] = 0; t.r_idx[c] = 0; pos_a[0] = c++;
+        t.r_isb[c] = 1; t.r_idx[c] = 0; pos_b[0] = c++;
+      } else {
+        if (i < NT) { t.r_isb[c] = 1; t.r_idx[c] = i; pos_b[i] = c++; }
+        if (i < MT) { t.r_isb[c] = 0; t.r_idx[c] = i; pos_a[i] = c++; }
+      }
+    }
+    // selection sort of the (m, n) pairs by the later of their two request positions
+    bool used[kMfma] = {};
+    for (int i = 0; i < kMfma; ++i) {
+      int best = -1, best_key = 0;
+      for (int q = 0; q < kMfma; ++q) {
+        if (used[q]) continue;
+        const int m = q / NT, n = q % NT;
+        const int key = (pos_a[m] > pos_b[n] ? pos_a[m] : pos_b[n]) * kMfma + q;
+        if (best < 0 || key < best_key) { best = q; best_key = key; }
+      }
+      used[best] = true;
+      t.mm[i] = best / NT;
+      t.nn[i] = best % NT;
+      t.need[i] = best_key / kMfma;
+    }
+    return t;
+  }
+  static constexpr Tables t = make();
+};
+
 template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 struct MfmaTile {
   static constexpr int kThreads = 64 * WM * WN;
@@ -101,6 +176,7 @@ struct MfmaTile {
   static_assert(BM % (RPI * kWaves) == 0 && BN % (RPI * kWaves) == 0, "slab rows must divide over waves");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave block must be a multiple of 32x32");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+  static_assert(NSTAGE >= 2, "the hand-over waits assume at least two stages");
 };
 
 template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
@@ -145,19 +221,24 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     b_off[q] = (uint32_t)(((int64_t)rr * p.ldb + c * 8) * 2);
   }
 
-  auto issue_loads = [&](int kt, int stage) {
-    const char* ga = (const char*)Ab + (int64_t)kt * (BK * 2);
-    const char* gb = (const char*)Bb + (int64_t)kt * (BK * 2);
-    unsigned char* sa = smem + stage * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024);
-    unsigned char* sb = smem + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024);
-#pragma unroll
-    for (int q = 0; q < Cfg::A_LOADS; ++q)
+  // One direct-to-LDS load: q < A_LOADS fills the A slab, the rest the B slab.
+  auto issue_one_load = [&](int q, int kt, int stage) {
+    if (q < Cfg::A_LOADS) {
+      const char* ga = (const char*)Ab + (int64_t)kt * (BK * 2);
+      unsigned char* sa = smem + stage * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024);
       __builtin_amdgcn_global_load_lds((global_cvoid_t*)(ga + a_off[q]),
                                        (lds_void_t*)(sa + q * 1024), 16, 0, 0);
+    } else {
+      const int qb = q - Cfg::A_LOADS;
+      const char* gb = (const char*)Bb + (int64_t)kt * (BK * 2);
+      unsigned char* sb = smem + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(gb + b_off[qb]),
+                                       (lds_void_t*)(sb + qb * 1024), 16, 0, 0);
+    }
+  };
+  auto issue_loads = [&](int kt, int stage) {
 #pragma unroll
-    for (int q = 0; q < Cfg::B_LOADS; ++q)
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(gb + b_off[q]),
-                                       (lds_void_t*)(sb + q * 1024), 16, 0, 0);
+    for (int q = 0; q < Cfg::A_LOADS + Cfg::B_LOADS; ++q) issue_one_load(q, kt, stage);
   };
 
   // K tail: the last slab may hold fewer than BK valid columns.  Chunks past K
@@ -211,63 +292,66 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // Fragment registers, double-buffered over the MFMA k-steps of a slab: while the
   // MFMAs of step kk run, the LDS reads of step kk+1 are already in flight.
   frag_t af[2][MT], bf[2][NT];
+  typedef StepOrder<MT, NT> Ord;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_uchar_t*)smem;
 
+  auto read_one = [&](int i, int stage, int kk, int buf) {       // i-th read of the fixed read order
+    const uint32_t s = smem_base + stage * Cfg::STAGE_BYTES;
+    const int idx = Ord::t.r_idx[i];
+    if (Ord::t.r_isb[i]) lds_read_b128(bf[buf][idx], s + b_rd[kk], idx * (32 * BK * 2));
+    else lds_read_b128(af[buf][idx], s + a_rd[kk], idx * (32 * BK * 2));
+  };
   auto read_frags = [&](int stage, int kk, int buf) {
-    const unsigned char* s = smem + stage * Cfg::STAGE_BYTES;
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
-      af[buf][m] = *(const frag_t*)(s + a_rd[kk] + m * (32 * BK * 2));
-#pragma unroll
-    for (int n = 0; n < NT; ++n)
-      bf[buf][n] = *(const frag_t*)(s + b_rd[kk] + n * (32 * BK * 2));
+    for (int i = 0; i < Ord::kReads; ++i) read_one(i, stage, kk, buf);
   };
-  // Operands swapped (B fragment first) so that each lane ends up holding one row
+
+  // One MFMA k-step on fragment buffer `cur`, instruction order pinned.  The wave
+  // issues in order (and, in the 4-wave shapes, alone on its SIMD), so a wait costs
+  // MFMA time: the reads for the next step (slab stage `rs`, k-step `rk`) go out one
+  // behind each of the first MFMAs, first-needed operands first, and the MFMAs run in
+  // the order in which their operands were requested one step earlier, so that every
+  // read has almost a whole step to land.  With `loads`, the direct-to-LDS loads of
+  // slab `lk` into stage `ls` follow the reads, spread over the remaining MFMAs.
+  // Operands go in swapped (B fragment first) so that a lane ends up holding one row
   // of C and runs of 4 consecutive columns: that is what the stores want.
-  auto mfma_step = [&](int buf) {
-#pragma unroll
-    for (int m = 0; m < MT; ++m)
-#pragma unroll
-      for (int n = 0; n < NT; ++n)
-        acc[m][n] = Frag<T>::mfma(bf[buf][n], af[buf][m], acc[m][n]);
-  };
-  // The wave issues in order and runs alone on its SIMD, so every wait it hits is
-  // MFMA time lost.  Pin the instruction order: the LDS reads of the next step go
-  // out one per MFMA at the start of the current step, which leaves the rest of the
-  // step's MFMAs to cover their latency; at a hand-over the reads of the new slab
-  // go first and the global loads that refill the freed stage follow, two per MFMA.
-  auto interleave = [&]() {
-    constexpr int kReads = MT + NT, kMfma = MT * NT;
-#pragma unroll
-    for (int i = 0; i < kReads; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
-    }
-    if (kMfma > kReads) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
-  };
-  auto interleave_hand_over = [&]() {
-    constexpr int kReads = MT + NT, kMfma = MT * NT;
+  auto step = [&](int cur, bool reads, int rs, int rk, bool loads, int lk, int ls) {
     constexpr int kLoads = Cfg::A_LOADS + Cfg::B_LOADS;
+    constexpr int kLeft = Ord::kMfma > Ord::kReads ? Ord::kMfma - Ord::kReads : 1;
+    constexpr int kPer = (kLoads + kLeft - 1) / kLeft;
 #pragma unroll
-    for (int i = 0; i < kReads; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
-    }
-    constexpr int kLeft = kMfma > kReads ? kMfma - kReads : 1;
-    constexpr int per = (kLoads + kLeft - 1) / kLeft;
+    for (int i = 0; i < Ord::kMfma; ++i) {
+      const int m = Ord::t.mm[i], n = Ord::t.nn[i];
+      // LDS reads return in order: the operands of MFMA i were requested at position
+      // need[i] of the previous step's kReads requests; since then the rest of those
+      // and min(i, kReads) requests of this step have been issued.
+      {
+        const int after = (Ord::kReads - 1 - Ord::t.need[i]) + (reads ? (i < Ord::kReads ? i : Ord::kReads) : 0);
+        wait_lgkmcnt_dyn(after);
+      }
+      Frag<T>::mfma(bf[cur][n], af[cur][m], acc[m][n]);
+      if (reads && i < Ord::kReads) read_one(i, rs, rk, cur ^ 1);
+      if (loads) {
+        const int j = Ord::kMfma > Ord::kReads ? i - Ord::kReads : i;
+        if (j >= 0) {
 #pragma unroll
-    for (int i = 0; i < kLeft; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x020, per, 0); // global -> LDS loads
+          for (int q = j * kPer; q < (j + 1) * kPer && q < kLoads; ++q) issue_one_load(q, lk, ls);
+        }
+      }
     }
   };
 
   // ---- main loop ------------------------------------------------------------------
-  // Slab t lives in LDS stage t % NSTAGE.  The hand-over to slab t+1 happens before
-  // the last MFMA step of slab t (whose fragments are already in registers), so
-  // the barrier and the first fragment reads of slab t+1 hide behind those MFMAs,
-  // and stage t % NSTAGE is refilled with slab t+NSTAGE right after the barrier.
-  const int T_full = p.K / BK;                 // slabs loaded direct-to-LDS
-  const int T_all = (p.K + BK - 1) / BK;       // + possibly one tail slab
+  // Full slabs (all BK columns valid) 0 .. T_full-1 run through a branch-free loop;
+  // slab t lives in LDS stage t % NSTAGE.  The hand-over to slab t+1 happens before
+  // the last MFMA step of slab t (whose fragments are already in registers), so the
+  // barrier and the first fragment reads of slab t+1 hide behind those MFMAs, and
+  // stage t % NSTAGE is refilled with slab t+NSTAGE right after the barrier.  Past
+  // the end the refill re-loads the last full slab into a stage nobody reads again:
+  // every iteration then issues the same number of loads, the wait counts are
+  // constants, and the loop body has no branch in it.  A K tail (K % BK != 0) is
+  // multiplied after the loop.
+  const int T_full = p.K / BK;
   constexpr int kLoadsPerSlab = Cfg::A_LOADS + Cfg::B_LOADS;
   constexpr int D = NSTAGE;                    // prefetch distance in slabs
   constexpr int KK = Cfg::KK;
@@ -278,54 +362,44 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // waves meet.
   auto hand_over = [&](auto later) {
     constexpr int kLater = decltype(later)::value;
-    __builtin_amdgcn_sched_barrier(0);         // nothing is scheduled across this point
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLater * kLoadsPerSlab) : "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
   };
-  typedef std::integral_constant<int, 0> none_later;
 
+  if (T_full > 0) {
 #pragma unroll
-  for (int s = 0; s < D; ++s) {
-    if (s < T_full) issue_loads(s, s);
-    else if (s < T_all) issue_loads_tail(s, s);
+    for (int s = 0; s < D; ++s) issue_loads(min(s, T_full - 1), s);
+    hand_over(std::integral_constant<int, D - 1>());
+    read_frags(0, 0, 0);
+    int stage = 0;
+    for (int t = 0; t < T_full; ++t) {
+      const int next_stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+#pragma unroll
+      for (int kk = 0; kk < KK - 1; ++kk) step(kk & 1, true, stage, kk + 1, false, 0, 0);
+      hand_over(std::integral_constant<int, D - 2>());
+      step((KK - 1) & 1, true, next_stage, 0, true, min(t + D, T_full - 1), stage);
+      stage = next_stage;
+    }
+    // the re-loads past the end and the last fragment reads are still in flight
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   }
-  if (D <= T_full) hand_over(std::integral_constant<int, D - 1>());
-  else hand_over(none_later());
-  read_frags(0, 0, 0);
-
-  // steady state: slab t+D exists and is a full slab
-  int t = 0;
-  for (; t + D < T_full; ++t) {
-    const int stage = t % NSTAGE;
+  if (T_full * BK < p.K) {                     // K tail, through registers with zero fill
+    __builtin_amdgcn_s_barrier();              // every wave is done with the LDS stages
+    asm volatile("" ::: "memory");
+    issue_loads_tail(T_full, 0);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    const int ksteps = (p.K - T_full * BK + 15) / 16;
 #pragma unroll
-    for (int kk = 0; kk < KK - 1; ++kk) {
-      read_frags(stage, kk + 1, (kk + 1) & 1);
-      mfma_step(kk & 1);
-      interleave();
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk < ksteps) {
+        read_frags(0, kk, 0);
+        step(0, false, 0, 0, false, 0, 0);
+      }
     }
-    hand_over(std::integral_constant<int, (D >= 2 ? D - 2 : 0)>());
-    read_frags((t + 1) % NSTAGE, 0, 0);
-    issue_loads(t + D, (t + D) % NSTAGE);
-    mfma_step((KK - 1) & 1);
-    interleave_hand_over();
-  }
-  // drain: the remaining (at most D, plus a tail) slabs
-  for (; t < T_all; ++t) {
-    const int stage = t % NSTAGE;
-#pragma unroll
-    for (int kk = 0; kk < KK - 1; ++kk) {
-      read_frags(stage, kk + 1, (kk + 1) & 1);
-      mfma_step(kk & 1);
-      interleave();
-    }
-    if (t + 1 < T_all) {
-      hand_over(none_later());
-      if (t + D < T_all) issue_loads_tail(t + D, (t + D) % NSTAGE);   // only a tail slab can be left
-      read_frags((t + 1) % NSTAGE, 0, 0);
-    }
-    mfma_step((KK - 1) & 1);
+    wait_lgkmcnt<0>();
   }
 
   // ---- epilogue ---------------------------------------------------------------------
