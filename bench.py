@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--workload", default="square_8192", choices=sorted(wl.WORKLOADS))
     ap.add_argument("--config", default=None, help="tile configuration name (default: built-in choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling HBM byte counters under a profiler)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -145,6 +147,14 @@ def main():
     def step(i):
         j = i % nbuf
         g.gemm_run(plan, Ad[j], Bd[j], Cd[j], biasd, stream)
+
+    if args.copy_calibration:
+        # a plain copy of known size: reads 1 GiB and writes 1 GiB
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)

@@ -44,19 +44,41 @@ __host__ __device__ inline int epilogue_activation(int e) {
   }
 }
 
+// GELU in fp32 with a handful of instructions (the epilogue runs on every output
+// element while the matrix cores idle, so it has to be short).
+//
+// erf form: erf(|x|) = 1 - (a1 s + ... + a5 s^5) exp(-x^2), s = 1/(1 + p|x|), the
+// five-term rational approximation of Abramowitz & Stegun (7.1.26), |error| <= 1.5e-7,
+// evaluated with the hardware reciprocal and exp2.  For negative arguments
+// 1 + erf(x) is formed as the tail itself, so nothing cancels.
+__device__ __forceinline__ float gelu_erf_f32(float t) {
+  const float x = t * 0.70710678118654752440f;
+  const float ax = fabsf(x);
+  const float s = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float poly = fmaf(s, 1.061405429f, -1.453152027f);
+  poly = fmaf(s, poly, 1.421413741f);
+  poly = fmaf(s, poly, -0.284496736f);
+  poly = fmaf(s, poly, 0.254829592f);
+  poly *= s;
+  const float tail = poly * __builtin_amdgcn_exp2f(-1.4426950408889634f * ax * ax);  // 1 - erf(|x|)
+  const float one_plus_erf = x < 0.0f ? tail : 2.0f - tail;
+  return 0.5f * t * one_plus_erf;
+}
+// tanh form: 1 + tanh(u) = 2 e / (e + 1) with e = exp(2u)  (no cancellation for u < 0).
+__device__ __forceinline__ float gelu_tanh_f32(float t) {
+  const float u = 0.79788456080286535588f * fmaf(0.044715f * t, t * t, t);
+  const float e = __builtin_amdgcn_exp2f(fminf(2.0f * 1.4426950408889634f * u, 126.0f));
+  const float one_plus_tanh = 2.0f * e * __builtin_amdgcn_rcpf(e + 1.0f);
+  return 0.5f * t * one_plus_tanh;
+}
+
 // act(t) in fp32.  `act` is uniform over the launch.
 __device__ __forceinline__ float apply_activation(int act, float t) {
   switch (act) {
-    case kActRelu:
-      return fmaxf(t, 0.0f);
-    case kActGeluErf:
-      return 0.5f * t * (1.0f + erff(t * 0.70710678118654752440f));
-    case kActGeluTanh: {
-      float u = 0.79788456080286535588f * (t + 0.044715f * t * t * t);
-      return 0.5f * t * (1.0f + tanhf(u));
-    }
-    default:
-      return t;
+    case kActRelu: return fmaxf(t, 0.0f);
+    case kActGeluErf: return gelu_erf_f32(t);
+    case kActGeluTanh: return gelu_tanh_f32(t);
+    default: return t;
   }
 }
 

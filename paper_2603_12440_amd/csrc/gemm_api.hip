@@ -22,7 +22,7 @@ using namespace mi355gemm;
 
 namespace {
 
-enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2 };
+enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_MFMA = 3 };
 
 struct Config;
 
@@ -44,7 +44,7 @@ typedef hipError_t (*launch_fn)(const gemm_plan&, const void*, const void*, void
 struct Config {
   const char* name;
   Kind kind;
-  int bm, bn, bk;         // tile (skinny: bm = padded M, bn = rows of W per wave, bk = 512)
+  int bm, bn, bk;         // tile (skinny: bm = padded M, bn = workgroups per CU, bk = K per pass)
   int threads;
   int lds_bytes;
   launch_fn launch[3];    // per storage dtype (GEMM_F32 / BF16 / F16); NULL = not compiled
@@ -104,7 +104,7 @@ hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* 
   return hipGetLastError();
 }
 
-template <typename T, int MB, int RPW, int WAVES>
+template <typename T, int MB, int WAVES>
 hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void* C,
                          const void* bias, hipStream_t s) {
   const gemm_desc_t& d = pl.d;
@@ -117,7 +117,24 @@ hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
   a.y_f32 = d.dtype_c == GEMM_F32;
-  skinny_gemm_kernel<T, MB, RPW, WAVES><<<pl.grid, pl.block, 0, s>>>(a);
+  skinny_gemm_kernel<T, MB, WAVES><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+template <typename T, int RB, int UNROLL>
+hipError_t launch_skinny_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
+                              const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  SkinnyArgs a;
+  a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
+  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
+  a.ldx = d.lda; a.ldw = d.ldb; a.ldy = d.ldc;
+  a.stride_x = d.stride_a; a.stride_w = d.stride_b; a.stride_y = d.stride_c;
+  a.stride_bias = d.stride_bias;
+  a.has_bias = epilogue_has_bias(d.epilogue);
+  a.act = epilogue_activation(d.epilogue);
+  a.y_f32 = d.dtype_c == GEMM_F32;
+  skinny_mfma_kernel<T, RB, UNROLL><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
 
@@ -135,23 +152,32 @@ hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void
     { nullptr, launch_mfma<bf16_t, BM, BN, BK, WM, WN, NS>,                                \
       launch_mfma<f16_t, BM, BN, BK, WM, WN, NS> } }
 
-#define SKINNY_CFG(MB, RPW, WAVES)                                                         \
-  { "skinny_m" #MB "_r" #RPW "_w" #WAVES, KIND_SKINNY, MB, RPW, 512, 64 * WAVES, 0,        \
-    { nullptr, launch_skinny<bf16_t, MB, RPW, WAVES>, launch_skinny<f16_t, MB, RPW, WAVES> } }
+// bn = workgroups per CU the grid is sized for
+#define SKINNY_CFG(MB, WAVES, PER_CU)                                                      \
+  { "skinny_m" #MB "_w" #WAVES "_g" #PER_CU, KIND_SKINNY, MB, PER_CU, kSkinnyKC,           \
+    64 * WAVES, MB <= 2 ? 16 : MB * kSkinnyKC * 2,                                         \
+    { nullptr, launch_skinny<bf16_t, MB, WAVES>, launch_skinny<f16_t, MB, WAVES> } }
+
+// skinny on the matrix cores: bm = 16 x rows, bn = rows of W per workgroup, bk = k per MFMA
+#define SKINNY_MFMA_CFG(RB, UNROLL)                                                        \
+  { "skinnymfma_r" #RB "_u" #UNROLL, KIND_SKINNY_MFMA, 16, 16 * RB, 32, 256, 4 * RB * 64 * 16, \
+    { nullptr, launch_skinny_mfma<bf16_t, RB, UNROLL>, launch_skinny_mfma<f16_t, RB, UNROLL> } }
 
 const Config kConfigs[] = {
     SIMT_CFG(64, 64, 16),
     SIMT_CFG(32, 32, 16),
+    MFMA_CFG(256, 256, 64, 2, 4, 2),
     MFMA_CFG(256, 256, 64, 2, 2, 2),
     MFMA_CFG(256, 256, 32, 2, 2, 4),
-    MFMA_CFG(256, 256, 64, 2, 4, 2),
     MFMA_CFG(256, 128, 64, 2, 2, 2),
     MFMA_CFG(128, 128, 64, 2, 2, 2),
-    SKINNY_CFG(1, 4, 4),
-    SKINNY_CFG(2, 4, 4),
-    SKINNY_CFG(4, 4, 4),
-    SKINNY_CFG(8, 2, 4),
-    SKINNY_CFG(16, 1, 4),
+    SKINNY_CFG(1, 4, 1),
+    SKINNY_CFG(2, 4, 1),
+    SKINNY_CFG(4, 4, 1),
+    SKINNY_CFG(8, 4, 1),
+    SKINNY_MFMA_CFG(1, 8),
+    SKINNY_MFMA_CFG(1, 16),
+    SKINNY_MFMA_CFG(2, 8),
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -219,7 +245,7 @@ bool applicable(const Config& c, const gemm_desc_t& d) {
   if (d.M >= ((int64_t)1 << 31) - 512 || d.N >= ((int64_t)1 << 31) - 512 ||
       d.K >= ((int64_t)1 << 31) - 512)
     return false;
-  if (c.kind == KIND_SKINNY) return d.M <= c.bm;
+  if (c.kind == KIND_SKINNY || c.kind == KIND_SKINNY_MFMA) return d.M <= c.bm;
   // MFMA: per-lane byte offsets inside a tile's row panel are 32-bit.
   if ((int64_t)c.bm * d.lda * 2 >= ((int64_t)1 << 32) || (int64_t)c.bn * d.ldb * 2 >= ((int64_t)1 << 32))
     return false;
@@ -236,8 +262,13 @@ int find_config(const char* name) {
 // Built-in choice.  MFMA tile: the largest tile whose grid still fills the 256 CUs
 // in whole rounds reasonably well (wave quantisation), biggest tile on ties.
 int choose(const gemm_desc_t& d) {
-  // skinny: smallest padded M that fits
-  if (d.M <= 16) {
+  // skinny: up to 4 rows of x on the vector ALUs (smallest padded M that fits, first
+  // such entry of the table), up to 16 on the matrix cores
+  if (d.M > 4 && d.M <= 16) {
+    const int i = find_config("skinnymfma_r1_u8");
+    if (i >= 0 && applicable(kConfigs[i], d)) return i;
+  }
+  if (d.M <= 4) {
     int best = -1;
     for (int i = 0; i < kNumConfigs; ++i)
       if (kConfigs[i].kind == KIND_SKINNY && applicable(kConfigs[i], d) &&
@@ -279,12 +310,19 @@ int fill_launch_shape(gemm_plan& pl) {
     pl.grid = dim3((unsigned)(tm * tn), (unsigned)d.batch, 1);
     pl.group_m = (int)(tm < 8 ? tm : 8);
     pl.xcd_remap = ((tm * tn) % 8 == 0) ? 1 : 0;
+  } else if (c.kind == KIND_SKINNY_MFMA) {
+    const int64_t blocks = (d.N + c.bn - 1) / c.bn;
+    const int64_t want = (int64_t)kNumCUs * 2;
+    pl.grid = dim3((unsigned)(blocks < want ? blocks : want), (unsigned)d.batch, 1);
   } else {
+    // One row of W per wave at a time, rows dealt round-robin: bn workgroups per CU,
+    // more only if a wave would otherwise own more rows than the kernel has slots for.
     const int waves = c.threads / 64;
-    const int64_t groups = (d.N + c.bn - 1) / c.bn;
-    int64_t wgs = (groups + waves - 1) / waves;
-    const int64_t cap = (int64_t)kNumCUs * 8;        // grid-stride beyond this
-    if (wgs > cap) wgs = cap;
+    int64_t wgs = (d.N + waves - 1) / waves;                       // one row per wave
+    const int64_t want = (int64_t)kNumCUs * c.bn;
+    if (wgs > want) wgs = want;
+    const int64_t need = (d.N + (int64_t)waves * kSkinnyMaxRows - 1) / ((int64_t)waves * kSkinnyMaxRows);
+    if (wgs < need) wgs = need;
     pl.grid = dim3((unsigned)wgs, (unsigned)d.batch, 1);
   }
   return GEMM_OK;

@@ -404,57 +404,124 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
 
   // ---- epilogue ---------------------------------------------------------------------
   // Lane l of a 32x32 accumulator tile holds row (l % 32) and, in register r,
-  // column 8*(r/4) + 4*(l/32) + r%4.
+  // column 8*(r/4) + 4*(l/32) + r%4: runs of only 4 columns per lane.  Storing those
+  // directly makes every store instruction touch 64 different cache lines with 8 or 16
+  // bytes each.  For 16-bit output each wave therefore passes its block through its
+  // own piece of the (now idle) LDS: 8-byte writes in accumulator order, 16-byte reads
+  // in row order, and the global stores cover whole 128-byte lines.
   const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
   const int act = p.act;
-  const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C & 15) == 0) && (p.stride_c % 4 == 0);
+
+  // bias of the 4 columns j .. j+3 (zero past N)
+  auto bias4 = [&](int j, float (&bv)[4]) {
 #pragma unroll
-  for (int m = 0; m < MT; ++m) {
-    const int i = row0 + wm * Cfg::WTM + m * 32 + fr;
+    for (int e = 0; e < 4; ++e) bv[e] = 0.0f;
+    if (!bias) return;
+    if (j + 3 < p.N) {
+      const f32x4_t b4 = *(const f32x4_t*)(bias + j);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bv[e] = b4[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (j + e < p.N) bv[e] = bias[j + e];
+    }
+  };
+
+  const bool through_lds = !p.c_f32 && (p.ldc % 8 == 0) && (p.stride_c % 8 == 0) &&
+                           (((uintptr_t)p.C & 15) == 0);
+  constexpr int ROWB = Cfg::WTN * 2;           // bytes per row of the wave's block
+  constexpr int CH = ROWB / 16;                // 16-byte chunks per row
+  constexpr int RPI2 = 64 / CH;                // rows one wave-wide 16-byte access covers
+  static_assert(Cfg::LDS_BYTES >= BM * BN * 2, "the output block must fit the slab stages");
+  static_assert(CH >= 8 && 64 % CH == 0, "row of the wave block: at least 128 bytes");
+  unsigned char* wt = smem + wave * (Cfg::WTM * ROWB);
+
+  // Each accumulator is read once: + bias, activation, rounding, and out (to LDS or
+  // to memory).  `actf` is a compile-time functor: one copy of the loops per activation.
+  auto drain = [&](auto actf) {
+    const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C & 15) == 0) && (p.stride_c % 4 == 0);
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int j = col0 + wn * Cfg::WTN + n * 32 + g * 8 + fh * 4;
-        if (i >= p.M || j >= p.N) continue;
-        float v[4];
+        float bv[4];
+        bias4(j, bv);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[m][n][g * 4 + e];
-        const bool full = (j + 3 < p.N);
-        if (bias) {
-          if (full) {
-            const f32x4_t bv = *(const f32x4_t*)(bias + j);
+        for (int m = 0; m < MT; ++m) {
+          float v[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += bv[e];
+          for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][g * 4 + e] + bv[e]);
+          if (through_lds) {
+            // chunk q of row r sits at chunk slot q ^ ((r >> 1) & 7): spreads the 32 rows
+            // a write instruction touches over the banks
+            const int r = m * 32 + fr, q = n * 4 + g;
+            u32x2_t w = {pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3])};
+            *(u32x2_t*)(wt + r * ROWB + ((q ^ ((r >> 1) & 7)) * 16) + fh * 8) = w;
           } else {
+            // fp32 output, or C rows that are not 16-byte aligned: store from the
+            // accumulator layout
+            const int i = row0 + wm * Cfg::WTM + m * 32 + fr;
+            if (i >= p.M || j >= p.N) continue;
+            const bool full = (j + 3 < p.N);
+            const int64_t o = batch * p.stride_c + (int64_t)i * p.ldc + j;
+            if (p.c_f32) {
+              float* c = (float*)p.C + o;
+              if (full && vec_ok) {
+                f32x4_t w = {v[0], v[1], v[2], v[3]};
+                *(f32x4_t*)c = w;
+              } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (j + e < p.N) v[e] += bias[j + e];
+                for (int e = 0; e < 4; ++e)
+                  if (j + e < p.N) c[e] = v[e];
+              }
+            } else {
+              T* c = (T*)p.C + o;
+              if (full && vec_ok) {
+                u32x2_t w = {pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3])};
+                *(u32x2_t*)c = w;
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  if (j + e < p.N) c[e] = from_float<T>(v[e]);
+              }
+            }
           }
         }
+      }
+    }
+  };
+
+  if (through_lds) {
+    __builtin_amdgcn_s_barrier();              // all waves are done reading the slab stages
+    asm volatile("" ::: "memory");
+  }
+  switch (act) {
+    case kActRelu: drain([](float t) { return fmaxf(t, 0.0f); }); break;
+    case kActGeluErf: drain([](float t) { return gelu_erf_f32(t); }); break;
+    case kActGeluTanh: drain([](float t) { return gelu_tanh_f32(t); }); break;
+    default: drain([](float t) { return t; }); break;
+  }
+  if (!through_lds) return;
+
+  T* Cb = (T*)p.C + batch * p.stride_c;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = apply_activation(act, v[e]);
-        const int64_t o = batch * p.stride_c + (int64_t)i * p.ldc + j;
-        if (p.c_f32) {
-          float* c = (float*)p.C + o;
-          if (full && vec_ok) {
-            f32x4_t w = {v[0], v[1], v[2], v[3]};
-            *(f32x4_t*)c = w;
-          } else {
+  for (int it = 0; it < Cfg::WTM / RPI2; ++it) {
+    const int r = it * RPI2 + lane / CH, q = lane % CH;
+    const u32x4_t val = *(const u32x4_t*)(wt + r * ROWB + ((q ^ ((r >> 1) & 7)) * 16));
+    const int i = row0 + wm * Cfg::WTM + r;
+    const int j = col0 + wn * Cfg::WTN + q * 8;
+    if (i < p.M && j < p.N) {
+      T* c = Cb + (int64_t)i * p.ldc + j;
+      if (j + 8 <= p.N) {
+        *(u32x4_t*)c = val;
+      } else {                                 // ragged right edge: element by element
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (j + e < p.N) c[e] = v[e];
-          }
-        } else {
-          T* c = (T*)p.C + o;
-          if (full && vec_ok) {
-            u32x2_t w = {pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3])};
-            *(u32x2_t*)c = w;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (j + e < p.N) c[e] = from_float<T>(v[e]);
-          }
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t word = val[e >> 1];
+          const uint16_t h = (e & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xffffu);
+          if (j + e < p.N) ((uint16_t*)c)[e] = h;
         }
       }
     }

@@ -95,8 +95,11 @@ def test_kernel_choice(g):
         return info
     assert "kernel=mfma_256x256" in kernel(M=8192, N=8192, K=8192)
     assert "grid=1024,1,1" in kernel(M=8192, N=8192, K=8192)
-    for m in (1, 4, 16):
-        assert "kernel=skinny" in kernel(M=m, N=8192, K=8192)
+    for m in (1, 4):
+        assert "kernel=skinny_m" in kernel(M=m, N=8192, K=8192)
+    for m in (5, 8, 16):
+        assert "kernel=skinnymfma" in kernel(M=m, N=8192, K=8192)
+    assert "grid=256,1,1" in kernel(M=1, N=8192, K=8192)
     assert "kernel=simt" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
     # 16-bit operands the tiled kernels cannot take go to the general kernel
     assert "kernel=simt" in kernel(M=256, N=256, K=256, layout_a=g.COL_MAJOR)
@@ -123,4 +126,4 @@ def test_config_table(g):
         g.gemm_create_config(d, len(names))
     d16 = g.GemmDesc(32, 4096, 4096)
     with pytest.raises(g.GemmError):                                # skinny kernels stop at M = 16
-        g.gemm_create_config(d16, names.index("skinny_m16_r1_w4"))
+        g.gemm_create_config(d16, names.index("skinnymfma_r1_u8"))

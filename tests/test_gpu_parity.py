@@ -34,11 +34,18 @@ def mfma_configs(g):
     return [n for n in g.config_names() if n.startswith("mfma")]
 
 
-def skinny_config_for(g, m):
-    for n in g.config_names():
-        if n.startswith("skinny_m") and int(n.split("_")[1][1:]) >= m:
-            return n
-    raise AssertionError(m)
+def skinny_configs(g, m):
+    """Every skinny-path configuration (vector-ALU or matrix-core) that takes M = m."""
+    out = []
+    for i, n in enumerate(g.config_names()):
+        if not n.startswith("skinny"):
+            continue
+        try:
+            g.gemm_destroy(g.gemm_create_config(g.GemmDesc(m, 64, 64), i))
+            out.append(n)
+        except g.GemmError:
+            pass
+    return out
 
 
 # ---- exact cases: small integers, every kernel family ---------------------------------
@@ -76,13 +83,15 @@ def test_mfma_exact_padded_and_fp16(g, oracle):
 
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 13, 16])
 def test_skinny_exact_small_integers(g, oracle, M):
-    cfg = skinny_config_for(g, M)
-    for (N, K) in [(1000, 520), (64, 8), (4099, 1024), (8, 4096)]:
-        w = wl.Workload("t", M, N, K, seed_a=M, seed_b=N)
-        exact_case(g, oracle, w, cfg, out_dtype="f32")
-    w = wl.Workload("t", M, 515, 136, seed_a=7, seed_b=8)
-    exact_case(g, oracle, w, cfg, pad_a=8, pad_b=8, pad_c=1)
-    exact_case(g, oracle, wl.scaled(w, dtype="f16", epilogue="bias_relu", seed_bias=3), cfg, out_dtype="f32")
+    cfgs = skinny_configs(g, M)
+    assert cfgs
+    for cfg in cfgs:
+        for (N, K) in [(1000, 520), (64, 8), (4099, 1024), (8, 4096), (300, 8200), (130, 16904), (2100, 1032)]:
+            w = wl.Workload("t", M, N, K, seed_a=M, seed_b=N)
+            exact_case(g, oracle, w, cfg, out_dtype="f32")
+        w = wl.Workload("t", M, 515, 136, seed_a=7, seed_b=8)
+        exact_case(g, oracle, w, cfg, pad_a=8, pad_b=8, pad_c=1)
+        exact_case(g, oracle, wl.scaled(w, dtype="f16", epilogue="bias_relu", seed_bias=3), cfg, out_dtype="f32")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
@@ -104,8 +113,8 @@ def test_all_ones_gives_K(g, K):
     """Every k contributes exactly once (K and all partial sums are exact in fp32,
     and these K are exact in bf16)."""
     for (M, N, cfg) in [(256, 256, "mfma_256x256x64_w2x2_s2"), (256, 256, "mfma_256x256x32_w2x2_s4"),
-                        (130, 70, "mfma_128x128x64_w2x2_s2"), (1, 96, "skinny_m1_r4_w4"),
-                        (16, 33, "skinny_m16_r1_w4")]:
+                        (130, 70, "mfma_128x128x64_w2x2_s2"), (1, 96, "skinny_m1_w4_g1"),
+                        (8, 33, "skinny_m8_w4_g1"), (16, 33, "skinnymfma_r1_u8"), (9, 70, "skinnymfma_r2_u8")]:
         w = wl.Workload("t", M, N, K)
         say(f"all-ones {M}x{N}x{K} {cfg}")
         A = torch.ones((1, M, K), dtype=torch.bfloat16)
@@ -119,8 +128,10 @@ def test_one_hot_k_sweep_copies_columns_of_b(g):
     boundaries, so a dropped, duplicated or shifted k-slab cannot hide."""
     K = 328
     ks = [0, 1, 7, 8, 15, 16, 31, 32, 63, 64, 65, 127, 128, 191, 192, 255, 256, 319, 320, 327]
-    for cfg, M, N in [(c, 300, 260) for c in mfma_configs(g)] + [("skinny_m4_r4_w4", 4, 260),
-                                                                ("skinny_m16_r1_w4", 16, 70)]:
+    for cfg, M, N in [(c, 300, 260) for c in mfma_configs(g)] + [("skinny_m4_w4_g1", 4, 260),
+                                                                ("skinny_m8_w4_g1", 7, 70),
+                                                                ("skinnymfma_r1_u8", 16, 70),
+                                                                ("skinnymfma_r2_u8", 11, 100)]:
         w = wl.Workload("t", M, N, K, seed_b=77)
         say(f"one-hot {cfg}")
         A = wl.one_hot_columns(M, K, ks).unsqueeze(0)
@@ -188,7 +199,8 @@ def test_mfma_random_against_oracle(g, oracle, name, changes):
 @pytest.mark.parametrize("epilogue", ["none", "bias", "bias_relu", "bias_gelu_erf", "bias_gelu_tanh", "relu", "gelu_erf"])
 def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
     for (M, N, K, cfg) in [(260, 264, 136, "mfma_256x256x64_w2x2_s2"), (130, 140, 72, "mfma_128x128x64_w2x2_s2"),
-                           (3, 515, 264, "skinny_m4_r4_w4"), (16, 100, 1032, "skinny_m16_r1_w4"),
+                           (3, 515, 264, "skinny_m4_w4_g1"), (8, 100, 1032, "skinny_m8_w4_g1"),
+                           (16, 100, 1032, "skinnymfma_r1_u8"), (5, 70, 264, "skinnymfma_r2_u8"),
                            (70, 90, 50, "simt_64x64x16")]:
         # pre-activations of order 1 so that the activations' curved parts are exercised
         w = wl.Workload("t", M, N, K, dist_a=("normal", 1.0), dist_b=("normal", 1.5 / np.sqrt(K)),
@@ -247,7 +259,7 @@ def test_fp16_random(g, oracle):
 
 def test_batches_and_bias_strides(g, oracle):
     """Each batch reads its own slab; shared bias (stride 0) against one per batch."""
-    for cfg in ("mfma_128x128x64_w2x2_s2", "simt_64x64x16", "skinny_m4_r4_w4"):
+    for cfg in ("mfma_128x128x64_w2x2_s2", "simt_64x64x16", "skinny_m4_w4_g1", "skinnymfma_r1_u8"):
         M = 4 if cfg.startswith("skinny") else 96
         w = wl.Workload("t", M, 136, 72, batch=4, epilogue="bias_gelu_erf", seed_a=31, seed_b=32)
         A, B, _ = wl.make_inputs(w)
