@@ -49,6 +49,31 @@ def parse():
     return ap.parse_args()
 
 
+def source_hash():
+    """Hash of the kernel sources: counter readings taken for another version do not count."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2603_12440_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch (fetch + write) from the committed rocprofv3 counter summary,
+    or None if there is none for this workload and this version of the kernels."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    cur = source_hash()
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 5 and not line.startswith("#") and f[0] == workload and f[2] == cur:
+            return float(f[3]) + float(f[4])
+    return None
+
+
 def gpu_desc(g, w):
     dt = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16}
     lay = {"row": g.ROW_MAJOR, "col": g.COL_MAJOR}
@@ -189,7 +214,7 @@ def main():
                    "layout": f"A {w.layout_a}-major, B {w.layout_b}-major, C row-major",
                    "epilogue": w.epilogue, "plan": info, "buffers_rotated": nbuf},
         "roofline": {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": runit,
-                     "frac": round(achieved / peak, 4), "traffic": None},
+                     "frac": round(achieved / peak, 4), "traffic": measured_traffic(w.name)},
     }
     ok = True
     if not args.no_cpu_baseline:

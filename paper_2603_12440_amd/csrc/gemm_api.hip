@@ -166,6 +166,7 @@ hipError_t launch_skinny_mfma(const gemm_plan& pl, const void* A, const void* B,
 const Config kConfigs[] = {
     SIMT_CFG(64, 64, 16),
     SIMT_CFG(32, 32, 16),
+    SIMT_CFG(32, 32, 64),
     MFMA_CFG(256, 256, 64, 2, 4, 2),
     MFMA_CFG(256, 256, 64, 2, 2, 2),
     MFMA_CFG(256, 256, 32, 2, 2, 4),
@@ -259,8 +260,8 @@ int find_config(const char* name) {
   return -1;
 }
 
-// Built-in choice.  MFMA tile: the largest tile whose grid still fills the 256 CUs
-// in whole rounds reasonably well (wave quantisation), biggest tile on ties.
+// Built-in choice.  MFMA tile: cheapest under a small cost model (wave quantisation over
+// the 256 CUs, measured efficiency per tile shape); first entry of the table on ties.
 int choose(const gemm_desc_t& d) {
   // skinny: up to 4 rows of x on the vector ALUs (smallest padded M that fits, first
   // such entry of the table), up to 16 on the matrix cores
@@ -281,16 +282,21 @@ int choose(const gemm_desc_t& d) {
   for (int i = 0; i < kNumConfigs; ++i) {
     const Config& c = kConfigs[i];
     if (c.kind != KIND_MFMA || !applicable(c, d)) continue;
+    // time ~ rounds over the CUs * work per round / measured relative efficiency of the tile
+    // shape; a fixed per-tile cost (prologue latency, epilogue) is worth ~600 columns of K.
+    const int area = c.bm * c.bn;
+    const int per_cu = area <= 128 * 128 ? 2 : 1;                 // workgroups that fit one CU's LDS
+    const double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 128 ? 0.75 : 0.84);
     const double tiles = (double)((d.M + c.bm - 1) / c.bm) * (double)((d.N + c.bn - 1) / c.bn) * d.batch;
-    const double rounds = (double)(int64_t)((tiles + kNumCUs - 1) / kNumCUs);
-    // time ~ rounds * tile work / per-tile efficiency (bigger tiles reuse operands better)
-    const double eff = c.bm * c.bn >= 256 * 256 ? 1.0 : (c.bm * c.bn >= 256 * 128 ? 0.85 : 0.7);
-    const double cost = rounds * c.bm * c.bn / eff;
+    const double rounds = (double)(int64_t)((tiles + kNumCUs * per_cu - 1) / (kNumCUs * per_cu));
+    const double cost = rounds * area * per_cu / eff * ((double)d.K + 600.0);
     if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
   }
   if (best >= 0) return best;
   // general kernel: small tile for small problems so that more CUs get work
-  const int big = find_config("simt_64x64x16"), small = find_config("simt_32x32x16");
+  // (the small tile with the long K step for latency-bound problems: few trips through the
+  // load - barrier - multiply loop)
+  const int big = find_config("simt_64x64x16"), small = find_config("simt_32x32x64");
   const double tiles64 = (double)((d.M + 63) / 64) * (double)((d.N + 63) / 64) * d.batch;
   return tiles64 >= kNumCUs ? big : small;
 }

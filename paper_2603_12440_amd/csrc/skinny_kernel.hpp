@@ -151,11 +151,22 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
         }
       return;
     }
-    for (int e = tid; e < MB * (kSkinnyKC / 8); e += 64 * WAVES) {
+    // all loads first (they are L2 hits and come back quickly), then the LDS writes
+    constexpr int kPer = MB * (kSkinnyKC / 8) / (64 * WAVES);
+    static_assert(MB * (kSkinnyKC / 8) % (64 * WAVES) == 0, "x piece must divide over the workgroup");
+    u32x4_t v[kPer];
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int e = tid + u * (64 * WAVES);
       const int m = e / (kSkinnyKC / 8), c = e % (kSkinnyKC / 8);
-      u32x4_t v = {0u, 0u, 0u, 0u};
-      if (m < p.M && k0 + c * 8 < p.K) v = *(const u32x4_t*)(X + (int64_t)m * p.ldx + k0 + c * 8);
-      *(u32x4_t*)(xs + (m * kSkinnyKC + c * 8) * 2) = v;
+      v[u] = u32x4_t{0u, 0u, 0u, 0u};
+      if (m < p.M && k0 + c * 8 < p.K) v[u] = *(const u32x4_t*)(X + (int64_t)m * p.ldx + k0 + c * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int e = tid + u * (64 * WAVES);
+      const int m = e / (kSkinnyKC / 8), c = e % (kSkinnyKC / 8);
+      *(u32x4_t*)(xs + (m * kSkinnyKC + c * 8) * 2) = v[u];
     }
   };
 
@@ -165,9 +176,14 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
     u32x4_t w0[P], w1[P];
     float t[MB];
     int n = first;
-    if (n < p.N) load_row(w0, n, 0);          // get the stream going before x is staged
-    stage_x(0);
-    if (!kXInRegs) __syncthreads();
+    if (kXInRegs) {
+      if (n < p.N) load_row(w0, n, 0);        // get the stream going before x arrives
+      stage_x(0);
+    } else {
+      stage_x(0);                             // x loads are issued ahead of the W stream, so
+      if (n < p.N) load_row(w0, n, 0);        // waiting for them does not wait for W
+      __syncthreads();
+    }
     while (n < p.N) {
       const int n1 = n + step;
       if (n1 < p.N) load_row(w1, n1, 0);
