@@ -221,20 +221,20 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     b_off[q] = (uint32_t)(((int64_t)rr * p.ldb + c * 8) * 2);
   }
 
-  // One direct-to-LDS load: q < A_LOADS fills the A slab, the rest the B slab.
+  // One direct-to-LDS load: q < A_LOADS fills the A slab, the rest the B slab.  Issued as
+  // "scalar base + 32-bit lane offset" through inline assembly: the slab's base address is
+  // wave-uniform, so no vector ALU work is spent on 64-bit addresses in the MFMA stream.
+  // M0 carries the LDS destination of the wave (lane l lands at M0 + 16*l).
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_uchar_t*)smem;
   auto issue_one_load = [&](int q, int kt, int stage) {
-    if (q < Cfg::A_LOADS) {
-      const char* ga = (const char*)Ab + (int64_t)kt * (BK * 2);
-      unsigned char* sa = smem + stage * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(ga + a_off[q]),
-                                       (lds_void_t*)(sa + q * 1024), 16, 0, 0);
-    } else {
-      const int qb = q - Cfg::A_LOADS;
-      const char* gb = (const char*)Bb + (int64_t)kt * (BK * 2);
-      unsigned char* sb = smem + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(gb + b_off[qb]),
-                                       (lds_void_t*)(sb + qb * 1024), 16, 0, 0);
-    }
+    const bool is_a = q < Cfg::A_LOADS;
+    const int qq = is_a ? q : q - Cfg::A_LOADS;
+    const char* g = (const char*)(is_a ? Ab : Bb) + (int64_t)kt * (BK * 2);
+    const uint32_t dst = lds_base + stage * Cfg::STAGE_BYTES + (is_a ? 0 : Cfg::A_BYTES) +
+                         (wave * (is_a ? Cfg::A_LOADS : Cfg::B_LOADS) + qq) * 1024;
+    const uint32_t off = is_a ? a_off[qq] : b_off[qq];
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(dst), "v"(off), "s"(g) : "memory", "m0");
   };
   auto issue_loads = [&](int kt, int stage) {
 #pragma unroll
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // MFMAs of step kk run, the LDS reads of step kk+1 are already in flight.
   frag_t af[2][MT], bf[2][NT];
   typedef StepOrder<MT, NT> Ord;
-  const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_uchar_t*)smem;
+  const uint32_t smem_base = lds_base;
 
   auto read_one = [&](int i, int stage, int kk, int buf) {       // i-th read of the fixed read order
     const uint32_t s = smem_base + stage * Cfg::STAGE_BYTES;
