@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="square_8192", choices=sorted(wl.WORKLOADS))
     ap.add_argument("--config", default=None, help="tile configuration name (default: built-in choice)")
+    ap.add_argument("--tune", action="store_true",
+                    help="pick the tile configuration with gemm_tune (times every applicable one first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling HBM byte counters under a profiler)")
@@ -153,6 +155,10 @@ def main():
     A, B, bias = wl.make_inputs(w)
     desc = gpu_desc(g, w)
     cfg = -1 if args.config is None else g.config_names().index(args.config)
+    if args.tune:
+        odt0 = wl.TORCH_DTYPE[w.dtype]
+        cfg, _ = g.gemm_tune(desc, A.to(dev), B.to(dev), torch.empty((w.batch, w.M, w.N), dtype=odt0, device=dev),
+                             None if bias is None else bias.to(dev), min_seconds=0.2)
     plan = g.gemm_create_config(desc, cfg)
     info = plan.info()
 

@@ -14,8 +14,8 @@
  *
  * Plain C ABI: no exceptions, no C++ or torch types cross this boundary.
  * All matrix pointers are DEVICE pointers; descriptors and plans live on the
- * HOST.  The library never allocates device memory, never synchronises the
- * device and keeps no state between calls besides the plans it hands out.
+ * HOST.  The library never allocates device memory and keeps no state between
+ * calls besides the plans it hands out; only gemm_tune waits for the device.
  */
 #ifndef MI355GEMM_GEMM_H
 #define MI355GEMM_GEMM_H
@@ -115,6 +115,23 @@ const char* gemm_config_name(int config);      /* NULL if out of range; static s
  */
 int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C,
              const void* bias, void* hip_stream);
+
+/*
+ * gemm_tune - parameter tuning over the compiled tile instantiations (the paper's templated
+ * kernels, Sec. 3.4: every valid instantiation is evaluated, the best one wins, all results
+ * are reported back).  Runs the problem `desc` on the caller's device buffers with every
+ * configuration that can take it and times each one with the paper's protocol (App.
+ * "Benchmarking kernel runtime"): a few initial trials size the loops, then a warm-up of at
+ * least `min_seconds` and 10 launches, then a measurement of at least `min_seconds` and 10
+ * launches made of inner loops of >= min(0.01 s, min_seconds) between two synchronisations.
+ *   best_config   receives the index of the fastest configuration (pass it to gemm_create_config);
+ *   us_per_config NULL, or room for gemm_config_count() floats: mean microseconds per launch,
+ *                 negative for configurations that cannot run this problem.
+ * C is overwritten (with correct results).  Blocks until done: it synchronises `hip_stream`.
+ * Creates HIP events and nothing else; no device memory is allocated.
+ */
+int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, const void* bias,
+              void* hip_stream, double min_seconds, int* best_config, float* us_per_config);
 
 /* gemm_destroy - release a plan.  NULL is a no-op that returns GEMM_OK. */
 int gemm_destroy(gemm_plan_t* plan);

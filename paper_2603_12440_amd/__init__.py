@@ -6,6 +6,6 @@ from .binding import (  # noqa: F401
     EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
     EPI_RELU, EPI_GELU_ERF, EPILOGUES,
     GemmError, GemmDesc, Plan,
-    gemm_create, gemm_create_config, gemm_run, gemm_destroy, gemm_status_string,
+    gemm_create, gemm_create_config, gemm_run, gemm_tune, gemm_destroy, gemm_status_string,
     gemm_plan_info, gemm_config_count, gemm_config_name, config_names, library_path, load_library,
 )

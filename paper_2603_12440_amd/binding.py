@@ -78,6 +78,10 @@ def load_library():
     lib.gemm_config_name.argtypes = [ctypes.c_int]
     lib.gemm_run.restype = ctypes.c_int
     lib.gemm_run.argtypes = [ctypes.c_void_p] * 6
+    lib.gemm_tune.restype = ctypes.c_int
+    lib.gemm_tune.argtypes = [ctypes.POINTER(GemmDesc), ctypes.c_void_p, ctypes.c_void_p,
+                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double,
+                              ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
     lib.gemm_destroy.restype = ctypes.c_int
     lib.gemm_destroy.argtypes = [ctypes.c_void_p]
     lib.gemm_status_string.restype = ctypes.c_char_p
@@ -150,6 +154,22 @@ def gemm_run(plan: Plan, A, B, C, bias=None, stream: Optional[int] = None) -> No
         stream = torch.cuda.current_stream().cuda_stream
     _check(load_library().gemm_run(plan.handle, _dev_ptr(A), _dev_ptr(B), _dev_ptr(C),
                                    _dev_ptr(bias), stream or None))
+
+
+def gemm_tune(desc: GemmDesc, A, B, C, bias=None, stream: Optional[int] = None,
+              min_seconds: float = 1.0):
+    """Time every applicable tile configuration on the given device buffers; returns
+    (best_config_index, {config_name: microseconds per launch})."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    lib = load_library()
+    n = lib.gemm_config_count()
+    best = ctypes.c_int(-1)
+    us = (ctypes.c_float * n)()
+    _check(lib.gemm_tune(ctypes.byref(desc), _dev_ptr(A), _dev_ptr(B), _dev_ptr(C), _dev_ptr(bias),
+                         stream or None, float(min_seconds), ctypes.byref(best), us))
+    return best.value, {gemm_config_name(i): float(us[i]) for i in range(n) if us[i] >= 0}
 
 
 def gemm_destroy(plan: Optional[Plan]) -> None:

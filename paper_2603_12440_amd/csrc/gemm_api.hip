@@ -405,6 +405,71 @@ int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, con
   return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }
 
+int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, const void* bias,
+              void* hip_stream, double min_seconds, int* best_config, float* us_per_config) {
+  if (!desc || !A || !B || !C || !best_config) return GEMM_ERR_NULL;
+  *best_config = -1;
+  gemm_desc_t d;
+  int rc = resolve(desc, &d);
+  if (rc != GEMM_OK) return rc;
+  if (!(min_seconds >= 0.0)) min_seconds = 0.0;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_LAUNCH; }
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(e0); return GEMM_ERR_LAUNCH; }
+  const double inner_s = min_seconds < 0.01 ? min_seconds : 0.01;
+  double best_us = 0.0;
+  int status = GEMM_OK;
+
+  // n launches between two events; returns elapsed seconds (< 0 on failure)
+  auto timed = [&](const gemm_plan* pl, long n) -> double {
+    if (hipEventRecord(e0, stream) != hipSuccess) return -1.0;
+    for (long i = 0; i < n; ++i) {
+      int r = gemm_run(pl, A, B, C, bias, hip_stream);
+      if (r != GEMM_OK) { status = r; return -1.0; }
+    }
+    if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0;
+    return (double)ms * 1e-3;
+  };
+
+  for (int i = 0; i < kNumConfigs && status == GEMM_OK; ++i) {
+    if (us_per_config) us_per_config[i] = -1.0f;
+    if (!applicable(kConfigs[i], d)) continue;
+    gemm_plan_t* pl = nullptr;
+    if (gemm_create_config(desc, i, &pl) != GEMM_OK) continue;
+    // initial trials: rough runtime
+    double t = timed(pl, 3);
+    if (t < 0) { gemm_destroy(pl); if (status == GEMM_OK) status = GEMM_ERR_LAUNCH; break; }
+    double per = t / 3 > 1e-7 ? t / 3 : 1e-7;
+    long inner = (long)(inner_s / per) + 1;
+    // warm-up: at least min_seconds and 10 launches
+    long warm = (long)(min_seconds / per) + 1;
+    if (warm < 10) warm = 10;
+    if (timed(pl, warm) < 0) { gemm_destroy(pl); if (status == GEMM_OK) status = GEMM_ERR_LAUNCH; break; }
+    // measurement: inner loops until at least min_seconds and 10 launches
+    double total = 0.0;
+    long launches = 0;
+    bool failed = false;
+    while (total < min_seconds || launches < 10) {
+      double dt = timed(pl, inner);
+      if (dt < 0) { failed = true; break; }
+      total += dt;
+      launches += inner;
+    }
+    gemm_destroy(pl);
+    if (failed) { if (status == GEMM_OK) status = GEMM_ERR_LAUNCH; break; }
+    const double us = total / (double)launches * 1e6;
+    if (us_per_config) us_per_config[i] = (float)us;
+    if (*best_config < 0 || us < best_us) { *best_config = i; best_us = us; }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (status != GEMM_OK) { (void)hipGetLastError(); return status; }
+  return *best_config >= 0 ? GEMM_OK : GEMM_ERR_UNSUPPORTED;
+}
+
 int gemm_destroy(gemm_plan_t* plan) {
   delete plan;
   return GEMM_OK;

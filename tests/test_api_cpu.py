@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(g):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(gemm_[a-z_]+)\s*\(", header))
     assert {"gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
-            "gemm_create_config", "gemm_config_count", "gemm_config_name"} <= names
+            "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune"} <= names
     lib = ctypes.CDLL(g.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(g):
 
 def test_binding_exposes_the_same_names(g):
     for n in ("gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
-              "gemm_create_config", "gemm_config_count", "gemm_config_name"):
+              "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune"):
         assert callable(getattr(g, n))
 
 
@@ -82,6 +82,11 @@ def test_null_handling(g):
     q = g.gemm_create(g.GemmDesc(64, 64, 64, epilogue=g.EPI_BIAS))
     assert lib.gemm_run(q.handle, 16, 16, 16, None, None) == -1   # bias missing
     g.gemm_destroy(q)
+    best = ctypes.c_int(5)
+    assert lib.gemm_tune(None, 16, 16, 16, None, None, 0.0, ctypes.byref(best), None) == -1
+    assert lib.gemm_tune(ctypes.byref(g.GemmDesc(8, 8, 8)), 16, 16, 16, None, None, 0.0, None, None) == -1
+    assert lib.gemm_tune(ctypes.byref(g.GemmDesc(0, 8, 8)), 16, 16, 16, None, None, 0.0,
+                         ctypes.byref(best), None) == -2 and best.value == -1
     for s in range(-9, 1):
         assert g.gemm_status_string(s) not in ("", "unknown status")
     assert g.gemm_status_string(-99) == "unknown status"

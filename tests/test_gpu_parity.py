@@ -289,3 +289,54 @@ def test_misaligned_pointer_is_refused(g):
     g.gemm_run(plan, buf, buf, C)
     torch.cuda.synchronize()
     g.gemm_destroy(plan)
+
+
+def test_tuner_times_every_applicable_configuration(g, oracle):
+    """Parameter tuning (Sec. 3.4 of the paper): every instantiation that can run the problem
+    is timed, the reported best one is among them, and a plan made from it is correct."""
+    w = wl.scaled(wl.WORKLOADS["gelu_8192x16384x4096"], M=300, N=520, K=264)
+    A, B, bias = wl.make_inputs(w)
+    dev = torch.device("cuda:0")
+    Ad, Bd, bd = A.to(dev), B.to(dev), bias.to(dev)
+    Cd = torch.empty((1, w.M, w.N), dtype=torch.bfloat16, device=dev)
+    desc = gpu_desc(g, w)
+    say("tune", w)
+    best, times = g.gemm_tune(desc, Ad, Bd, Cd, bd, min_seconds=0.005)
+    names = g.config_names()
+    assert names[best] in times and times[names[best]] == min(times.values())
+    assert all(t > 0 for t in times.values())
+    assert {n for n in names if n.startswith("mfma") or n.startswith("simt")} == set(times)   # M = 300: no skinny
+    plan = g.gemm_create_config(desc, best)
+    g.gemm_run(plan, Ad, Bd, Cd, bd)
+    torch.cuda.synchronize()
+    g.gemm_destroy(plan)
+    ref = run_oracle(oracle, w, A, B, bias)
+    assert_parity(w, Cd.cpu(), ref, A, B, bias)
+
+
+# ---- full benchmark sizes, sampled ------------------------------------------------------------
+
+@pytest.mark.parametrize("name", sorted(wl.WORKLOADS))
+def test_full_size_workloads_on_sampled_outputs(g, oracle, name):
+    """Every benchmark workload at its full size, with the plan bench.py times (built-in
+    choice): sampled outputs (tile-lattice corners + random positions) against the oracle's
+    point evaluation, to the E1 tolerance and the E2 bound."""
+    from helpers import oracle_problem, e2_bound, E1_TOL
+    w = wl.WORKLOADS[name]
+    A, B, bias = wl.make_inputs(w)
+    say(f"full size {name}")
+    C, info = run_gpu(g, w, A, B, bias, return_plan_info=True)
+    say("   ", info)
+    pb, pi, pj = wl.sample_points(w, 3000, 1234)
+    ref = oracle.ref_gemm_points(oracle_problem(oracle, w), wl.storage_numpy(A), wl.storage_numpy(B),
+                                 None if bias is None else bias.numpy(), pb, pi, pj, want=("y", "t", "s"))
+    got = wl.to_float64(C)[pb, pi, pj]
+    err = np.abs(got - ref["y"])
+    scale = w.K * float(A.abs().max()) * float(B.abs().max()) + (float(bias.abs().max()) if bias is not None else 0.0)
+    assert np.isfinite(got).all()
+    assert err.max() / scale <= E1_TOL[w.dtype]
+    assert np.all(err <= e2_bound(w, ref)), float((err / e2_bound(w, ref)).max())
+    # properties that hold at any size: nothing left unwritten (the sentinel would show), and the
+    # paper's relative criterion on the sampled entries
+    eps = 1e-3 * float(np.sqrt(np.mean(ref["y"] ** 2))) + 1e-30
+    assert np.mean(err / (np.abs(ref["y"]) + eps) < 0.01) >= 0.99
