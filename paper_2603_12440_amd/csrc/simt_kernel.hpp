@@ -25,6 +25,7 @@ struct SimtArgs {
 
 template <typename TIn, typename TOut, int TM, int TN, int TK>
 __global__ __launch_bounds__(256) void simt_gemm_kernel(SimtArgs p) {
+  static_assert((TM * TK) % 256 == 0 && (TN * TK) % 256 == 0, "slab must divide over 256 lanes");
   constexpr int RM = TM / 16, RN = TN / 16;      // register block per lane
   constexpr int PAD = 4;
   __shared__ float As[TK][TM + PAD];
@@ -49,26 +50,52 @@ __global__ __launch_bounds__(256) void simt_gemm_kernel(SimtArgs p) {
   const bool a_k_fast = (p.a_sk == 1);
   const bool b_k_fast = (p.b_sk == 1);
 
-  for (int64_t k0 = 0; k0 < p.K; k0 += TK) {
+  // The next slab's global loads are issued before the current slab is multiplied
+  // (registers as the second buffer), so that their latency overlaps the arithmetic.
+  constexpr int A_PER = TM * TK / 256, B_PER = TN * TK / 256;
+  float ra[A_PER], rb[B_PER];
+  auto fetch = [&](int64_t k0) {
 #pragma unroll
-    for (int e = tid; e < TM * TK; e += 256) {
+    for (int u = 0; u < A_PER; ++u) {
+      const int e = tid + u * 256;
       int i, k;
       if (a_k_fast) { i = e / TK; k = e % TK; } else { k = e / TM; i = e % TM; }
-      float v = 0.0f;
+      ra[u] = 0.0f;
       if (i0 + i < p.M && k0 + k < p.K)
-        v = to_float<TIn>(A[(i0 + i) * p.a_si + (k0 + k) * p.a_sk]);
-      As[k][i] = v;
+        ra[u] = to_float<TIn>(A[(i0 + i) * p.a_si + (k0 + k) * p.a_sk]);
     }
 #pragma unroll
-    for (int e = tid; e < TN * TK; e += 256) {
+    for (int u = 0; u < B_PER; ++u) {
+      const int e = tid + u * 256;
       int j, k;
       if (b_k_fast) { j = e / TK; k = e % TK; } else { k = e / TN; j = e % TN; }
-      float v = 0.0f;
+      rb[u] = 0.0f;
       if (j0 + j < p.N && k0 + k < p.K)
-        v = to_float<TIn>(B[(k0 + k) * p.b_sk + (j0 + j) * p.b_sj]);
-      Bs[k][j] = v;
+        rb[u] = to_float<TIn>(B[(k0 + k) * p.b_sk + (j0 + j) * p.b_sj]);
     }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int u = 0; u < A_PER; ++u) {
+      const int e = tid + u * 256;
+      int i, k;
+      if (a_k_fast) { i = e / TK; k = e % TK; } else { k = e / TM; i = e % TM; }
+      As[k][i] = ra[u];
+    }
+#pragma unroll
+    for (int u = 0; u < B_PER; ++u) {
+      const int e = tid + u * 256;
+      int j, k;
+      if (b_k_fast) { j = e / TK; k = e % TK; } else { k = e / TN; j = e % TN; }
+      Bs[k][j] = rb[u];
+    }
+  };
+
+  fetch(0);
+  for (int64_t k0 = 0; k0 < p.K; k0 += TK) {
+    stash();
     __syncthreads();
+    if (k0 + TK < p.K) fetch(k0 + TK);
 #pragma unroll
     for (int k = 0; k < TK; ++k) {
       float a[RM], w[RN];

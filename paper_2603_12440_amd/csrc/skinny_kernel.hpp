@@ -284,7 +284,8 @@ __global__ __launch_bounds__(256) void skinny_mfma_kernel(SkinnyArgs p) {
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
           wv[u][r] = u32x4_t{0u, 0u, 0u, 0u};
-          if (live) wv[u][r] = __builtin_nontemporal_load((const u32x4_t*)(wrow[r] + k));
+          // (plain loads: the other half of each 128-byte line is wanted by the next step)
+          if (live) wv[u][r] = *(const u32x4_t*)(wrow[r] + k);
         }
         xv[u] = u32x4_t{0u, 0u, 0u, 0u};
         if (live && x_live) xv[u] = *(const u32x4_t*)(xrow + k);
