@@ -22,7 +22,7 @@ using namespace mi355gemm;
 
 namespace {
 
-enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_MFMA = 3 };
+enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_MFMA = 3, KIND_SKINNY_RING = 4 };
 
 struct Config;
 
@@ -138,6 +138,23 @@ hipError_t launch_skinny_mfma(const gemm_plan& pl, const void* A, const void* B,
   return hipGetLastError();
 }
 
+template <typename T, int NS>
+hipError_t launch_skinny_ring(const gemm_plan& pl, const void* A, const void* B, void* C,
+                              const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  SkinnyArgs a;
+  a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
+  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
+  a.ldx = d.lda; a.ldw = d.ldb; a.ldy = d.ldc;
+  a.stride_x = d.stride_a; a.stride_w = d.stride_b; a.stride_y = d.stride_c;
+  a.stride_bias = d.stride_bias;
+  a.has_bias = epilogue_has_bias(d.epilogue);
+  a.act = epilogue_activation(d.epilogue);
+  a.y_f32 = d.dtype_c == GEMM_F32;
+  skinny_ring_kernel<T, NS><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
 // ---- the table of compiled instantiations ----------------------------------------------
 
 #define SIMT_CFG(TM, TN, TK)                                                               \
@@ -163,6 +180,11 @@ hipError_t launch_skinny_mfma(const gemm_plan& pl, const void* A, const void* B,
   { "skinnymfma_r" #RB "_u" #UNROLL, KIND_SKINNY_MFMA, 16, 16 * RB, 32, 256, 4 * RB * 64 * 16, \
     { nullptr, launch_skinny_mfma<bf16_t, RB, UNROLL>, launch_skinny_mfma<f16_t, RB, UNROLL> } }
 
+// skinny through wave-private LDS rings: bm = 16 x rows, bn = 32 rows of W per workgroup
+#define SKINNY_RING_CFG(NS)                                                                \
+  { "skinnyring_s" #NS, KIND_SKINNY_RING, 16, 32, 64, 256, 4 * NS * 6144,                   \
+    { nullptr, launch_skinny_ring<bf16_t, NS>, launch_skinny_ring<f16_t, NS> } }
+
 const Config kConfigs[] = {
     SIMT_CFG(64, 64, 16),
     SIMT_CFG(32, 32, 16),
@@ -179,6 +201,9 @@ const Config kConfigs[] = {
     SKINNY_MFMA_CFG(1, 8),
     SKINNY_MFMA_CFG(1, 16),
     SKINNY_MFMA_CFG(2, 8),
+    SKINNY_RING_CFG(5),
+    SKINNY_RING_CFG(4),
+    SKINNY_RING_CFG(6),
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -247,6 +272,9 @@ bool applicable(const Config& c, const gemm_desc_t& d) {
       d.K >= ((int64_t)1 << 31) - 512)
     return false;
   if (c.kind == KIND_SKINNY || c.kind == KIND_SKINNY_MFMA) return d.M <= c.bm;
+  if (c.kind == KIND_SKINNY_RING)   // 32-bit lane offsets inside a 32-row panel
+    return d.M <= c.bm && 32 * d.ldb * 2 < ((int64_t)1 << 32) && 32 * d.lda * 2 < ((int64_t)1 << 32) &&
+           (d.N + 31) / 32 < ((int64_t)1 << 31);
   // MFMA: per-lane byte offsets inside a tile's row panel are 32-bit.
   if ((int64_t)c.bm * d.lda * 2 >= ((int64_t)1 << 32) || (int64_t)c.bn * d.ldb * 2 >= ((int64_t)1 << 32))
     return false;
@@ -266,7 +294,7 @@ int choose(const gemm_desc_t& d) {
   // skinny: up to 4 rows of x on the vector ALUs (smallest padded M that fits, first
   // such entry of the table), up to 16 on the matrix cores
   if (d.M > 4 && d.M <= 16) {
-    const int i = find_config("skinnymfma_r1_u8");
+    const int i = find_config("skinnyring_s5");
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
   if (d.M <= 4) {
@@ -316,6 +344,8 @@ int fill_launch_shape(gemm_plan& pl) {
     pl.grid = dim3((unsigned)(tm * tn), (unsigned)d.batch, 1);
     pl.group_m = (int)(tm < 8 ? tm : 8);
     pl.xcd_remap = ((tm * tn) % 8 == 0) ? 1 : 0;
+  } else if (c.kind == KIND_SKINNY_RING) {
+    pl.grid = dim3((unsigned)((d.N + c.bn - 1) / c.bn), (unsigned)d.batch, 1);
   } else if (c.kind == KIND_SKINNY_MFMA) {
     const int64_t blocks = (d.N + c.bn - 1) / c.bn;
     const int64_t want = (int64_t)kNumCUs * 2;

@@ -324,4 +324,163 @@ __global__ __launch_bounds__(256) void skinny_mfma_kernel(SkinnyArgs p) {
   }
 }
 
+
+// ---- M up to 16, weights through wave-private LDS rings -----------------------------------
+// The 16x16x32 variant above reads 64 bytes of 16 different rows per load instruction; the
+// memory system prefers whole 128-byte lines.  Here a workgroup owns 32 rows of W, its four
+// waves split K into contiguous quarters, and every wave runs its own ring of NSTAGE slabs
+// (32 rows x 64 columns of W, and the matching 64 columns of up to 16 x rows) filled by
+// direct-to-LDS loads that move full lines, 8 rows per instruction.  The ring is private to
+// the wave, so the K loop needs no workgroup barrier, only vmcnt waits.  Products by
+// v_mfma_f32_32x32x16 (x rows past M are clamped copies and never stored); the four partial
+// 32x32 blocks are added through LDS at the end.
+typedef float f32x16acc_t __attribute__((ext_vector_type(16)));
+template <typename T> struct Mfma32;
+template <> struct Mfma32<bf16_t> {
+  static __device__ __forceinline__ f32x16acc_t run(const u32x4_t& a, const u32x4_t& b, f32x16acc_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mfma32<f16_t> {
+  static __device__ __forceinline__ f32x16acc_t run(const u32x4_t& a, const u32x4_t& b, f32x16acc_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a),
+                                                  __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  }
+};
+
+template <typename T, int NSTAGE>
+__global__ __launch_bounds__(256) void skinny_ring_kernel(SkinnyArgs p) {
+  constexpr int kSlab = 6144;                          // bytes per stage: W 32 x 128 B, then x 16 x 128 B
+  constexpr int kLoads = 6;                            // direct-to-LDS loads per slab and wave
+  typedef __attribute__((address_space(3))) unsigned char lds_uchar;
+  static_assert(4 * NSTAGE * kSlab >= 4 * 16 * 64 * 4, "the rings double as the reduction buffer");
+  __shared__ __attribute__((aligned(1024))) unsigned char ring[4 * NSTAGE * kSlab];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t batch = blockIdx.y;
+  const T* X = (const T*)p.X + batch * p.stride_x;
+  const T* W = (const T*)p.W + batch * p.stride_w;
+  const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
+  const int n0 = blockIdx.x * 32;
+
+  // slab row r, 16-byte chunk c lives at chunk slot c ^ swz(r) of its 128-byte row
+  auto swz = [](int r) { return (r & 7) ^ ((r >> 3) & 3); };
+  // loads: instruction q covers slab rows 8q .. 8q+7; lane l writes row 8q + l/8, slot l%8
+  uint32_t w_off[4], x_off[2];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = q * 8 + lane / 8;
+    const int c = (lane % 8) ^ swz(r);
+    w_off[q] = (uint32_t)(((int64_t)min(n0 + r, p.N - 1) - n0) * p.ldw * 2 + c * 16);
+    if (q < 2) x_off[q] = (uint32_t)((int64_t)min(r, p.M - 1) * p.ldx * 2 + c * 16);
+  }
+  const char* Wb = (const char*)(W + (int64_t)n0 * p.ldw);
+  const char* Xb = (const char*)X;
+  unsigned char* my_ring = ring + wave * (NSTAGE * kSlab);
+  const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_uchar*)my_ring;
+
+  auto issue_slab = [&](int s, int stage) {            // full slab s (64 columns from 64 s)
+    const char* gw = Wb + (int64_t)s * 128;
+    const char* gx = Xb + (int64_t)s * 128;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(ring_lds + stage * kSlab + q * 1024), "v"(w_off[q]), "s"(gw) : "memory", "m0");
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(ring_lds + stage * kSlab + 4096 + q * 1024), "v"(x_off[q]), "s"(gx) : "memory", "m0");
+  };
+
+  // fragments: MFMA 32x32x16 operand lane l = row l%32, k-octet l/32
+  const int fr = lane & 31, fh = lane >> 5;
+  // (x has 16 rows in LDS: the upper half of the x operand repeats them; those outputs are dropped)
+  uint32_t rd[4], rdx[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    rd[kk] = fr * 128 + (((kk * 2 + fh) ^ swz(fr)) * 16);
+    rdx[kk] = (fr & 15) * 128 + (((kk * 2 + fh) ^ swz(fr & 15)) * 16);
+  }
+
+  f32x16acc_t acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+
+  auto multiply = [&](int stage, int ksteps) {
+    const unsigned char* s = my_ring + stage * kSlab;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk < ksteps) {
+        const u32x4_t wf = *(const u32x4_t*)(s + rd[kk]);
+        const u32x4_t xf = *(const u32x4_t*)(s + 4096 + rdx[kk]);
+        acc = Mfma32<T>::run(xf, wf, acc);             // D[x row][W row]
+      }
+    }
+  };
+
+  const int s_full = p.K / 64;                         // full slabs, split over the four waves
+  const int per_wave = (s_full + 3) / 4;
+  const int s_begin = min(wave * per_wave, s_full);
+  const int s_end = min(s_full, s_begin + per_wave);
+  if (s_begin < s_end) {
+#pragma unroll
+    for (int i = 0; i < NSTAGE - 1; ++i) issue_slab(min(s_begin + i, s_end - 1), i);
+    int stage = 0;
+    for (int s = s_begin; s < s_end; ++s) {
+      // slab s has landed when at most the NSTAGE-2 slabs issued after it are outstanding
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * kLoads) : "memory");
+      // refill the stage the previous iteration multiplied from (its reads have been
+      // consumed by MFMAs already issued); past the end, re-load the last slab: same count
+      issue_slab(min(s + NSTAGE - 1, s_end - 1), stage == 0 ? NSTAGE - 1 : stage - 1);
+      multiply(stage, 4);
+      stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  if (wave == 3 && s_full * 64 < p.K) {
+    // K tail: zero-filled slab through registers into stage 0 of this wave's ring
+    const int k0 = s_full * 64, kvalid = p.K - k0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r = q * 8 + lane / 8;
+      const int c = (lane % 8) ^ swz(r);
+      u32x4_t wv = {0u, 0u, 0u, 0u}, xv = {0u, 0u, 0u, 0u};
+      if (c * 8 < kvalid) {
+        wv = *(const u32x4_t*)(Wb + (int64_t)s_full * 128 + w_off[q]);
+        if (q < 2) xv = *(const u32x4_t*)(Xb + (int64_t)s_full * 128 + x_off[q]);
+      }
+      *(u32x4_t*)(my_ring + q * 1024 + lane * 16) = wv;
+      if (q < 2) *(u32x4_t*)(my_ring + 4096 + q * 1024 + lane * 16) = xv;
+    }
+    multiply(0, (kvalid + 15) / 16);
+  }
+
+  // add the four K quarters (the rings are free now), then bias, activation, store
+  __syncthreads();
+  float* red = (float*)ring;                           // [4 waves][16 regs][64 lanes]
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
+  __syncthreads();
+  // wave w finishes accumulator registers 4w .. 4w+3: x rows 8w + 4*(lane/32) + e, column lane%32
+  // (waves 2 and 3 hold only the repeated rows 16 .. 31 and store nothing)
+  const int n = n0 + fr;
+  const float bv = (bias && n < p.N) ? bias[n] : 0.0f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int r = wave * 4 + e;
+    const float t = red[(0 * 16 + r) * 64 + lane] + red[(1 * 16 + r) * 64 + lane] +
+                    red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
+    const int m = 8 * wave + 4 * fh + e;
+    if (m < p.M && n < p.N) {
+      const float v = apply_activation(p.act, t + bv);
+      const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
+      if (p.y_f32) ((float*)p.Y)[o] = v;
+      else ((T*)p.Y)[o] = from_float<T>(v);
+    }
+  }
+}
+
 }  // namespace mi355gemm
