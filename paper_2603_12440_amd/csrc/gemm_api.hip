@@ -34,6 +34,11 @@ struct gemm_plan {
   int cfg_index;
   dim3 grid, block;
   int group_m, xcd_remap; // MFMA scheduling
+  // Optional second launch for the columns past d.N (a different tile shape for the part of
+  // the problem that does not fill whole rounds of the CUs): its own plan, and the element
+  // offsets of its B, C and bias.
+  gemm_plan* tail;
+  int64_t tail_off_b, tail_off_c, tail_off_bias;
 };
 
 namespace {
@@ -288,6 +293,55 @@ int find_config(const char* name) {
   return -1;
 }
 
+// Cost model of one MFMA tile shape on an M x N x K (x batch) problem:
+// time ~ rounds over the CUs * work per round / measured relative efficiency of the tile
+// shape; a fixed per-tile cost (prologue latency, epilogue) is worth ~600 columns of K.
+// In these units one microsecond is about 2.7e6.
+double mfma_cost(const Config& c, int64_t M, int64_t N, int64_t K, int64_t batch) {
+  const int area = c.bm * c.bn;
+  const int per_cu = area <= 128 * 128 ? 2 : 1;                 // workgroups that fit one CU's LDS
+  const double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 128 ? 0.75 : 0.84);
+  const double tiles = (double)((M + c.bm - 1) / c.bm) * (double)((N + c.bn - 1) / c.bn) * (double)batch;
+  const double rounds = (double)(int64_t)((tiles + kNumCUs * per_cu - 1) / (kNumCUs * per_cu));
+  return rounds * area * per_cu / eff * ((double)K + 600.0);
+}
+
+int best_mfma(const gemm_desc_t& d, double* cost_out) {
+  int best = -1;
+  double best_cost = 0;
+  for (int i = 0; i < kNumConfigs; ++i) {
+    const Config& c = kConfigs[i];
+    if (c.kind != KIND_MFMA || !applicable(c, d)) continue;
+    const double cost = mfma_cost(c, d.M, d.N, d.K, d.batch);
+    if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
+  }
+  if (cost_out) *cost_out = best_cost;
+  return best;
+}
+
+// Wave quantisation: when the 256x256 tiles of a problem fill some whole rounds of the 256
+// CUs and then a partial one, give the whole rounds to the big tile and the remaining
+// columns to whatever tile shape suits them best (usually 128x128, two per CU).  Returns
+// the number of leading columns for the first launch, or 0 for "do not split".
+int64_t split_columns(const gemm_desc_t& d, int big, double single_cost) {
+  if (big < 0 || d.batch != 1) return 0;
+  const Config& c = kConfigs[big];
+  if (c.bm != 256 || c.bn != 256) return 0;
+  const int64_t tiles_m = (d.M + c.bm - 1) / c.bm, tiles_n = (d.N + c.bn - 1) / c.bn;
+  if (tiles_m > kNumCUs || kNumCUs % tiles_m != 0) return 0;
+  const int64_t cols_per_round = kNumCUs / tiles_m;
+  const int64_t cols_big = tiles_n / cols_per_round * cols_per_round;
+  if (cols_big == 0 || cols_big == tiles_n) return 0;
+  const int64_t n_first = cols_big * c.bn;
+  gemm_desc_t rest = d;
+  rest.N = d.N - n_first;
+  double rest_cost = 0;
+  if (best_mfma(rest, &rest_cost) < 0) return 0;
+  const double launch = 3.0 * 2.7e6;
+  const double split_cost = mfma_cost(c, d.M, n_first, d.K, 1) + rest_cost + launch;
+  return split_cost < 0.97 * single_cost ? n_first : 0;
+}
+
 // Built-in choice.  MFMA tile: cheapest under a small cost model (wave quantisation over
 // the 256 CUs, measured efficiency per tile shape); first entry of the table on ties.
 int choose(const gemm_desc_t& d) {
@@ -305,21 +359,7 @@ int choose(const gemm_desc_t& d) {
         best = i;
     if (best >= 0) return best;
   }
-  int best = -1;
-  double best_cost = 0;
-  for (int i = 0; i < kNumConfigs; ++i) {
-    const Config& c = kConfigs[i];
-    if (c.kind != KIND_MFMA || !applicable(c, d)) continue;
-    // time ~ rounds over the CUs * work per round / measured relative efficiency of the tile
-    // shape; a fixed per-tile cost (prologue latency, epilogue) is worth ~600 columns of K.
-    const int area = c.bm * c.bn;
-    const int per_cu = area <= 128 * 128 ? 2 : 1;                 // workgroups that fit one CU's LDS
-    const double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 128 ? 0.75 : 0.84);
-    const double tiles = (double)((d.M + c.bm - 1) / c.bm) * (double)((d.N + c.bn - 1) / c.bn) * d.batch;
-    const double rounds = (double)(int64_t)((tiles + kNumCUs * per_cu - 1) / (kNumCUs * per_cu));
-    const double cost = rounds * area * per_cu / eff * ((double)d.K + 600.0);
-    if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
-  }
+  const int best = best_mfma(d, nullptr);
   if (best >= 0) return best;
   // general kernel: small tile for small problems so that more CUs get work
   // (the small tile with the long K step for latency-bound problems: few trips through the
@@ -400,6 +440,7 @@ int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_pl
   int rc = resolve(desc, &d);
   if (rc != GEMM_OK) return rc;
   if (config < -1 || config >= kNumConfigs) return GEMM_ERR_BAD_CONFIG;
+  const bool auto_choice = config == -1;
   if (config == -1) config = choose(d);
   if (config < 0) return GEMM_ERR_UNSUPPORTED;
   if (!applicable(kConfigs[config], d)) return GEMM_ERR_BAD_CONFIG;
@@ -408,8 +449,36 @@ int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_pl
   pl->d = d;
   pl->cfg = &kConfigs[config];
   pl->cfg_index = config;
+  pl->tail = nullptr;
+  pl->tail_off_b = pl->tail_off_c = pl->tail_off_bias = 0;
+  if (auto_choice && kConfigs[config].kind == KIND_MFMA) {
+    double single_cost = 0;
+    best_mfma(d, &single_cost);
+    int big = -1;                                   // the first 256x256 shape of the table
+    for (int i = 0; i < kNumConfigs && big < 0; ++i)
+      if (kConfigs[i].kind == KIND_MFMA && kConfigs[i].bm == 256 && kConfigs[i].bn == 256 &&
+          applicable(kConfigs[i], d))
+        big = i;
+    const int64_t n_first = split_columns(d, big, single_cost);
+    if (n_first > 0) {
+      config = big;
+      pl->cfg = &kConfigs[config];
+      pl->cfg_index = config;
+      // second launch: columns n_first .. N-1 (rows of the N x K weight matrix, columns of C)
+      gemm_desc_t rest = d;
+      rest.N = d.N - n_first;
+      gemm_plan_t* tail = nullptr;
+      if (gemm_create_config(&rest, best_mfma(rest, nullptr), &tail) == GEMM_OK) {
+        pl->tail = tail;
+        pl->tail_off_b = n_first * d.ldb;
+        pl->tail_off_c = n_first;
+        pl->tail_off_bias = n_first;
+        pl->d.N = n_first;
+      }
+    }
+  }
   rc = fill_launch_shape(*pl);
-  if (rc != GEMM_OK) { delete pl; return rc; }
+  if (rc != GEMM_OK) { gemm_destroy(pl); return rc; }
   *out_plan = pl;
   return GEMM_OK;
 }
@@ -432,7 +501,16 @@ int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, con
   int rc = check_device();
   if (rc != GEMM_OK) return rc;
   hipError_t e = plan->cfg->launch[d.dtype_a](*plan, A, B, C, bias, (hipStream_t)hip_stream);
-  return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
+  if (e != hipSuccess) return GEMM_ERR_LAUNCH;
+  if (plan->tail) {
+    const gemm_plan* t = plan->tail;
+    const char* B2 = (const char*)B + plan->tail_off_b * esize(d.dtype_b);
+    char* C2 = (char*)C + plan->tail_off_c * esize(d.dtype_c);
+    const float* bias2 = bias ? (const float*)bias + plan->tail_off_bias : nullptr;
+    e = t->cfg->launch[d.dtype_a](*t, A, B2, C2, bias2, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return GEMM_ERR_LAUNCH;
+  }
+  return GEMM_OK;
 }
 
 int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, const void* bias,
@@ -501,6 +579,7 @@ int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, co
 }
 
 int gemm_destroy(gemm_plan_t* plan) {
+  if (plan) delete plan->tail;
   delete plan;
   return GEMM_OK;
 }
@@ -524,6 +603,14 @@ const char* gemm_status_string(int status) {
 int gemm_plan_info(const gemm_plan_t* plan, char* buf, size_t n) {
   if (!plan || (!buf && n)) return GEMM_ERR_NULL;
   const Config& c = *plan->cfg;
+  if (plan->tail) {
+    const Config& t = *plan->tail->cfg;
+    return std::snprintf(buf, n, "kernel=%s tile=%dx%dx%d grid=%u,%u,%u block=%u lds=%d columns=0..%lld "
+                         "+ kernel=%s grid=%u,%u,%u columns=%lld..", c.name, c.bm, c.bn, c.bk,
+                         plan->grid.x, plan->grid.y, plan->grid.z, plan->block.x, c.lds_bytes,
+                         (long long)plan->d.N - 1, t.name, plan->tail->grid.x, plan->tail->grid.y,
+                         plan->tail->grid.z, (long long)plan->d.N);
+  }
   return std::snprintf(buf, n, "kernel=%s tile=%dx%dx%d grid=%u,%u,%u block=%u lds=%d", c.name,
                        c.bm, c.bn, c.bk, plan->grid.x, plan->grid.y, plan->grid.z, plan->block.x,
                        c.lds_bytes);

@@ -344,3 +344,19 @@ def test_full_size_workloads_on_sampled_outputs(g, oracle, name):
     # paper's relative criterion on the sampled entries
     eps = 1e-3 * float(np.sqrt(np.mean(ref["y"] ** 2))) + 1e-30
     assert np.mean(err / (np.abs(ref["y"]) + eps) < 0.01) >= 0.99
+
+
+def test_split_plan_two_launches(g, oracle):
+    """Shapes whose 256x256 tiles do not fill whole rounds of the CUs are planned as two
+    launches (big tiles for the full rounds, another shape for the remaining columns): the
+    seam must be invisible.  Integer data: bit exact; bias + ReLU across the seam."""
+    w = wl.Workload("t", 4096, 6144, 1024, epilogue="bias_relu", seed_a=3, seed_b=4, seed_bias=5)
+    sa, sb = wl.operand_shapes(w)
+    A = wl.small_integers(sa, 3, -1, 1)
+    B = wl.small_integers(sb, 4, -1, 1)
+    bias = wl.small_integers((w.N,), 5, -3, 3, "f32")
+    C, info = run_gpu(g, w, A, B, bias, return_plan_info=True, pad_c=8, out_dtype="f32")
+    say(info)
+    assert " + kernel=" in info
+    ref = run_oracle(oracle, w, A, B, bias, want=("y",))
+    assert np.array_equal(wl.to_float64(C), ref["y"])
