@@ -23,6 +23,7 @@ using namespace mi355gemm;
 namespace {
 
 enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_MFMA = 3, KIND_SKINNY_RING = 4 };
+// (KIND_SKINNY_RING also covers the register-staged kernel: same panel shape, grid and limits)
 
 struct Config;
 
@@ -160,6 +161,23 @@ hipError_t launch_skinny_ring(const gemm_plan& pl, const void* A, const void* B,
   return hipGetLastError();
 }
 
+template <typename T, int DEPTH, int RB>
+hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B, void* C,
+                               const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  SkinnyArgs a;
+  a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
+  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
+  a.ldx = d.lda; a.ldw = d.ldb; a.ldy = d.ldc;
+  a.stride_x = d.stride_a; a.stride_w = d.stride_b; a.stride_y = d.stride_c;
+  a.stride_bias = d.stride_bias;
+  a.has_bias = epilogue_has_bias(d.epilogue);
+  a.act = epilogue_activation(d.epilogue);
+  a.y_f32 = d.dtype_c == GEMM_F32;
+  skinny_stage_kernel<T, DEPTH, RB><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
 // ---- the table of compiled instantiations ----------------------------------------------
 
 #define SIMT_CFG(TM, TN, TK)                                                               \
@@ -185,6 +203,10 @@ hipError_t launch_skinny_ring(const gemm_plan& pl, const void* A, const void* B,
   { "skinnymfma_r" #RB "_u" #UNROLL, KIND_SKINNY_MFMA, 16, 16 * RB, 32, 256, 4 * RB * 64 * 16, \
     { nullptr, launch_skinny_mfma<bf16_t, RB, UNROLL>, launch_skinny_mfma<f16_t, RB, UNROLL> } }
 
+// skinny with W staged through registers into wave-private LDS slabs: same panel shape
+#define SKINNY_STAGE_CFG(DEPTH, RB)                                                        \
+  { "skinnystage_d" #DEPTH "_b" #RB, KIND_SKINNY_RING, 16, 32, RB / 2, 256, 4 * 48 * RB,     \
+    { nullptr, launch_skinny_stage<bf16_t, DEPTH, RB>, launch_skinny_stage<f16_t, DEPTH, RB> } }
 // skinny through wave-private LDS rings: bm = 16 x rows, bn = 32 rows of W per workgroup
 #define SKINNY_RING_CFG(NS)                                                                \
   { "skinnyring_s" #NS, KIND_SKINNY_RING, 16, 32, 64, 256, 4 * NS * 6144,                   \
@@ -209,6 +231,9 @@ const Config kConfigs[] = {
     SKINNY_RING_CFG(5),
     SKINNY_RING_CFG(4),
     SKINNY_RING_CFG(6),
+    SKINNY_STAGE_CFG(2, 256),
+    SKINNY_STAGE_CFG(3, 256),
+    SKINNY_STAGE_CFG(2, 512),
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -348,7 +373,10 @@ int choose(const gemm_desc_t& d) {
   // skinny: up to 4 rows of x on the vector ALUs (smallest padded M that fits, first
   // such entry of the table), up to 16 on the matrix cores
   if (d.M > 4 && d.M <= 16) {
-    const int i = find_config("skinnyring_s5");
+    // register-staged MFMA kernel: the long-burst variant when there is at most one
+    // workgroup per CU anyway, the lighter one (several workgroups per CU) otherwise
+    const bool one_round = (d.N + 31) / 32 <= kNumCUs;
+    const int i = find_config(one_round ? "skinnystage_d2_b512" : "skinnystage_d3_b256");
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
   if (d.M <= 4) {

@@ -74,6 +74,7 @@ constexpr int kSkinnyMaxRows = 32;               // rows one wave may own (the h
 template <typename T, int MB, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
   constexpr int P = kSkinnyPieces;
+  constexpr int DEPTH = 2;                       // rows a wave keeps requested (more gains nothing)
   // One or two x rows live in registers (each lane keeps the pieces it multiplies
   // with); more rows are staged in LDS and re-read for every row of W.
   constexpr bool kXInRegs = MB <= 2;
@@ -171,30 +172,30 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
   };
 
   if (n_pass == 1) {
-    // The common case: all of K in one pass.  Rows are double-buffered: the next
-    // row's loads are issued before the current row is multiplied.
-    u32x4_t w0[P], w1[P];
+    // The common case: all of K in one pass.  A wave keeps DEPTH rows requested: a
+    // row's registers are refilled with the row DEPTH steps on as soon as it has been
+    // multiplied.
+    u32x4_t w[DEPTH][P];
     float t[MB];
     int n = first;
-    if (kXInRegs) {
-      if (n < p.N) load_row(w0, n, 0);        // get the stream going before x arrives
-      stage_x(0);
-    } else {
-      stage_x(0);                             // x loads are issued ahead of the W stream, so
-      if (n < p.N) load_row(w0, n, 0);        // waiting for them does not wait for W
-      __syncthreads();
-    }
-    while (n < p.N) {
-      const int n1 = n + step;
-      if (n1 < p.N) load_row(w1, n1, 0);
-      dot_row(w0, t);
-      store_row(t, n);
-      if (n1 >= p.N) break;
-      const int n2 = n1 + step;
-      if (n2 < p.N) load_row(w0, n2, 0);
-      dot_row(w1, t);
-      store_row(t, n1);
-      n = n2;
+    if (!kXInRegs) stage_x(0);                // x loads go out ahead of the W stream, so
+                                              // waiting for them does not wait for W
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+      if (n + d * step < p.N) load_row(w[d], n + d * step, 0);
+    if (kXInRegs) stage_x(0); else __syncthreads();
+    bool more = n < p.N;
+    while (more) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        if (more) {
+          dot_row(w[d], t);
+          store_row(t, n);
+          if (n + DEPTH * step < p.N) load_row(w[d], n + DEPTH * step, 0);
+          n += step;
+          more = n < p.N;
+        }
+      }
     }
   } else {
     // Long K: pass by pass over x pieces of KC elements; the partial sums of a wave's
@@ -461,6 +462,170 @@ __global__ __launch_bounds__(256) void skinny_ring_kernel(SkinnyArgs p) {
   // add the four K quarters (the rings are free now), then bias, activation, store
   __syncthreads();
   float* red = (float*)ring;                           // [4 waves][16 regs][64 lanes]
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
+  __syncthreads();
+  // wave w finishes accumulator registers 4w .. 4w+3: x rows 8w + 4*(lane/32) + e, column lane%32
+  // (waves 2 and 3 hold only the repeated rows 16 .. 31 and store nothing)
+  const int n = n0 + fr;
+  const float bv = (bias && n < p.N) ? bias[n] : 0.0f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int r = wave * 4 + e;
+    const float t = red[(0 * 16 + r) * 64 + lane] + red[(1 * 16 + r) * 64 + lane] +
+                    red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
+    const int m = 8 * wave + 4 * fh + e;
+    if (m < p.M && n < p.N) {
+      const float v = apply_activation(p.act, t + bv);
+      const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
+      if (p.y_f32) ((float*)p.Y)[o] = v;
+      else ((T*)p.Y)[o] = from_float<T>(v);
+    }
+  }
+}
+
+// ---- M up to 16, W staged through registers ------------------------------------------
+// Same division of work as the ring kernel (a workgroup owns 32 rows of W, its four
+// waves split K into quarters, one 32x32x16 MFMA tile per wave, quarters added at the
+// end), but W and x travel global -> registers -> LDS: plain 16-byte loads in which 16
+// (or 32) lanes cover 256 (512) contiguous bytes of a row, DEPTH slabs requested ahead,
+// then ds_write_b128 into one wave-private, swizzled LDS slab from which the MFMA
+// fragments are read back.  For a stream that comes from HBM this moves more bytes per
+// microsecond than direct-to-LDS loads do.
+template <typename T, int DEPTH, int RB>
+__global__ __launch_bounds__(256) void skinny_stage_kernel(SkinnyArgs p) {
+  constexpr int kRowBytes = RB;                        // RB/2 columns per slab: 256 or 512 bytes of each row
+  constexpr int kCols = RB / 2;
+  constexpr int kWBytes = 32 * kRowBytes, kXBytes = 16 * kRowBytes;
+  constexpr int kLPR = RB / 16, kRPI = 64 / kLPR;      // lanes per row, rows per load instruction
+  constexpr int kWLoads = 32 / kRPI, kXLoads = 16 / kRPI;   // 16-byte loads per lane and slab
+  constexpr int kSteps = kCols / 16;                   // MFMAs per slab
+  static_assert(4 * (kWBytes + kXBytes) >= 4 * 16 * 64 * 4, "the slabs double as the reduction buffer");
+  __shared__ __attribute__((aligned(1024))) unsigned char slabs[4 * (kWBytes + kXBytes)];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t batch = blockIdx.y;
+  const T* X = (const T*)p.X + batch * p.stride_x;
+  const T* W = (const T*)p.W + batch * p.stride_w;
+  const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
+  const int n0 = blockIdx.x * 32;
+
+  // Load q of a slab: kLPR lanes cover one row's piece, lane l takes its 16-byte chunk
+  // l % kLPR of slab row kRPI q + l / kLPR.  In LDS the chunk sits at slot (chunk ^ row%16)
+  // of its row, for W and x alike (16 slots of 16 bytes span all banks).
+  const int lr = lane / kLPR, lc = lane % kLPR;
+  const char* w_src[kWLoads];
+  const char* x_src[kXLoads];
+  uint32_t w_dst[kWLoads], x_dst[kXLoads];
+#pragma unroll
+  for (int q = 0; q < kWLoads; ++q) {
+    const int r = kRPI * q + lr;
+    w_src[q] = (const char*)(W + (int64_t)min(n0 + r, p.N - 1) * p.ldw) + lc * 16;
+    w_dst[q] = r * kRowBytes + ((lc ^ (r & 15)) * 16);
+    if (q < kXLoads) {
+      x_src[q] = (const char*)(X + (int64_t)min(r, p.M - 1) * p.ldx) + lc * 16;
+      x_dst[q] = kWBytes + r * kRowBytes + ((lc ^ (r & 15)) * 16);
+    }
+  }
+  unsigned char* mine = slabs + wave * (kWBytes + kXBytes);
+
+  u32x4_t wv[DEPTH][kWLoads], xv[DEPTH][kXLoads];
+  // columns [kCols s, kCols s + kCols), all of them inside K
+  auto load_slab = [&](u32x4_t (&w)[kWLoads], u32x4_t (&x)[kXLoads], int s) {
+    const int64_t off = (int64_t)s * kRowBytes;
+#pragma unroll
+    for (int q = 0; q < kWLoads; ++q) w[q] = __builtin_nontemporal_load((const u32x4_t*)(w_src[q] + off));
+#pragma unroll
+    for (int q = 0; q < kXLoads; ++q) x[q] = *(const u32x4_t*)(x_src[q] + off);
+  };
+  auto write_slab = [&](const u32x4_t (&w)[kWLoads], const u32x4_t (&x)[kXLoads]) {
+#pragma unroll
+    for (int q = 0; q < kWLoads; ++q) *(u32x4_t*)(mine + w_dst[q]) = w[q];
+#pragma unroll
+    for (int q = 0; q < kXLoads; ++q) *(u32x4_t*)(mine + x_dst[q]) = x[q];
+  };
+
+  // fragments: MFMA 32x32x16 operand lane l = row l%32, k-octet l/32
+  // (x has 16 rows in LDS: the upper half of the x operand repeats them; those outputs are dropped)
+  const int fr = lane & 31, fh = lane >> 5;
+  f32x16acc_t acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  auto multiply = [&]() {
+#pragma unroll
+    for (int k0 = 0; k0 < kSteps; k0 += 8) {
+      u32x4_t wf[8], xf[8];                            // eight steps' reads first, then their MFMAs
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const int slot = (((k0 + kk) * 2 + fh) ^ (fr & 15)) * 16;
+        wf[kk] = *(const u32x4_t*)(mine + fr * kRowBytes + slot);
+        xf[kk] = *(const u32x4_t*)(mine + kWBytes + (fr & 15) * kRowBytes + slot);
+      }
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) acc = Mfma32<T>::run(xf[kk], wf[kk], acc);   // D[x row][W row]
+    }
+  };
+
+  const int s_full = p.K / kCols;                        // full slabs, split over the four waves
+  const int per_wave = (s_full + 3) / 4;
+  const int s_begin = min(wave * per_wave, s_full);
+  const int s_end = min(s_full, s_begin + per_wave);
+  int s = s_begin;
+  if (s_end - s_begin >= 2 * DEPTH) {
+    // Steady state: every refill is in range, so all loads are unconditional and the
+    // wait for a slab leaves the DEPTH-1 younger ones in flight.  (The scheduling
+    // barriers keep the next slab's LDS writes, and with them the wait for its loads,
+    // behind this slab's MFMAs.)
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) load_slab(wv[d], xv[d], s_begin + d);
+    for (; s + 2 * DEPTH <= s_end; s += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        write_slab(wv[d], xv[d]);
+        load_slab(wv[d], xv[d], s + d + DEPTH);
+        multiply();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+      if (s_begin + d < s_end) load_slab(wv[d], xv[d], s_begin + d);
+  }
+  // the last one or two rounds: registers d hold slab s + d (where that is below s_end)
+  for (; s < s_end; s += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      if (s + d < s_end) {
+        write_slab(wv[d], xv[d]);
+        if (s + d + DEPTH < s_end) load_slab(wv[d], xv[d], s + d + DEPTH);
+        multiply();
+      }
+    }
+  }
+  if (wave == 3 && s_full * kCols < p.K) {
+    // K tail: chunks past K are written as zeros
+    const bool live = s_full * kCols + lc * 8 < p.K;
+    const int64_t off = (int64_t)s_full * kRowBytes;
+#pragma unroll
+    for (int q = 0; q < kWLoads; ++q) {
+      wv[0][q] = u32x4_t{0u, 0u, 0u, 0u};
+      if (live) wv[0][q] = *(const u32x4_t*)(w_src[q] + off);
+    }
+#pragma unroll
+    for (int q = 0; q < kXLoads; ++q) {
+      xv[0][q] = u32x4_t{0u, 0u, 0u, 0u};
+      if (live) xv[0][q] = *(const u32x4_t*)(x_src[q] + off);
+    }
+    write_slab(wv[0], xv[0]);
+    multiply();
+  }
+
+  // add the four K quarters (the slabs are free now), then bias, activation, store
+  __syncthreads();
+  float* red = (float*)slabs;                          // [4 waves][16 regs][64 lanes]
 #pragma unroll
   for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
   __syncthreads();

@@ -103,7 +103,8 @@ def test_kernel_choice(g):
     for m in (1, 4):
         assert "kernel=skinny_m" in kernel(M=m, N=8192, K=8192)
     for m in (5, 8, 16):
-        assert "kernel=skinnyring" in kernel(M=m, N=8192, K=8192)
+        assert "kernel=skinnystage_d2_b512" in kernel(M=m, N=8192, K=8192)
+        assert "kernel=skinnystage_d3_b256" in kernel(M=m, N=28672, K=8192)
     assert "grid=256,1,1" in kernel(M=1, N=8192, K=8192)
     assert "kernel=simt" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
     # 16-bit operands the tiled kernels cannot take go to the general kernel

@@ -115,7 +115,8 @@ def test_all_ones_gives_K(g, K):
     for (M, N, cfg) in [(256, 256, "mfma_256x256x64_w2x2_s2"), (256, 256, "mfma_256x256x32_w2x2_s4"),
                         (130, 70, "mfma_128x128x64_w2x2_s2"), (1, 96, "skinny_m1_w4_g1"),
                         (8, 33, "skinny_m8_w4_g1"), (16, 33, "skinnymfma_r1_u8"), (9, 70, "skinnymfma_r2_u8"),
-                        (16, 70, "skinnyring_s5"), (3, 33, "skinnyring_s6")]:
+                        (16, 70, "skinnyring_s5"), (3, 33, "skinnyring_s6"),
+                        (16, 70, "skinnystage_d3_b256"), (3, 33, "skinnystage_d2_b512"), (9, 64, "skinnystage_d2_b256")]:
         w = wl.Workload("t", M, N, K)
         say(f"all-ones {M}x{N}x{K} {cfg}")
         A = torch.ones((1, M, K), dtype=torch.bfloat16)
@@ -134,7 +135,10 @@ def test_one_hot_k_sweep_copies_columns_of_b(g):
                                                                 ("skinnymfma_r1_u8", 16, 70),
                                                                 ("skinnymfma_r2_u8", 11, 100),
                                                                 ("skinnyring_s4", 16, 100),
-                                                                ("skinnyring_s6", 5, 70)]:
+                                                                ("skinnyring_s6", 5, 70),
+                                                                ("skinnystage_d2_b512", 16, 100),
+                                                                ("skinnystage_d3_b256", 5, 70),
+                                                                ("skinnystage_d2_b256", 13, 33)]:
         w = wl.Workload("t", M, N, K, seed_b=77)
         say(f"one-hot {cfg}")
         A = wl.one_hot_columns(M, K, ks).unsqueeze(0)
@@ -205,6 +209,8 @@ def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
                            (3, 515, 264, "skinny_m4_w4_g1"), (8, 100, 1032, "skinny_m8_w4_g1"),
                            (16, 100, 1032, "skinnymfma_r1_u8"), (5, 70, 264, "skinnymfma_r2_u8"),
                            (16, 100, 1032, "skinnyring_s4"), (7, 70, 264, "skinnyring_s6"),
+                           (16, 100, 1032, "skinnystage_d3_b256"), (7, 70, 264, "skinnystage_d2_b512"),
+                           (11, 40, 2120, "skinnystage_d2_b256"),
                            (70, 90, 50, "simt_64x64x16")]:
         # pre-activations of order 1 so that the activations' curved parts are exercised
         w = wl.Workload("t", M, N, K, dist_a=("normal", 1.0), dist_b=("normal", 1.5 / np.sqrt(K)),
@@ -263,7 +269,8 @@ def test_fp16_random(g, oracle):
 
 def test_batches_and_bias_strides(g, oracle):
     """Each batch reads its own slab; shared bias (stride 0) against one per batch."""
-    for cfg in ("mfma_128x128x64_w2x2_s2", "simt_64x64x16", "skinny_m4_w4_g1", "skinnymfma_r1_u8", "skinnyring_s4"):
+    for cfg in ("mfma_128x128x64_w2x2_s2", "simt_64x64x16", "skinny_m4_w4_g1", "skinnymfma_r1_u8", "skinnyring_s4",
+                "skinnystage_d3_b256"):
         M = 4 if cfg.startswith("skinny") else 96
         w = wl.Workload("t", M, 136, 72, batch=4, epilogue="bias_gelu_erf", seed_a=31, seed_b=32)
         A, B, _ = wl.make_inputs(w)
