@@ -6,7 +6,8 @@ package.  It shares no code with the GPU library and does not import it.
 from .ref import (  # noqa: F401
     DTYPE_F32, DTYPE_BF16, DTYPE_F16, ROW_MAJOR, COL_MAJOR,
     EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
-    EPI_RELU, EPI_GELU_ERF,
-    Problem, build, ref_gemm, ref_gemm_points, activation, num_threads,
+    EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
+    EPI_SWISH_SCALE, EPI_SIGMOID_SCALE_RESIDUAL,
+    Problem, build, ref_gemm, ref_gemm_points, activation, epilogue, sigmoid, num_threads,
     bf16_bits_to_double, f16_bits_to_double, f32_to_bf16_rne, f32_to_f16_rne,
 )

@@ -19,8 +19,10 @@ _LIB = os.path.join(_HERE, "libref_gemm.so")
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 ROW_MAJOR, COL_MAJOR = 0, 1
 (EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
- EPI_RELU, EPI_GELU_ERF) = range(7)
-_BIAS_EPILOGUES = (EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH)
+ EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
+ EPI_SWISH_SCALE, EPI_SIGMOID_SCALE_RESIDUAL) = range(11)
+_BIAS_EPILOGUES = (EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
+                   EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL)
 
 
 class _CProblem(ctypes.Structure):
@@ -32,6 +34,7 @@ class _CProblem(ctypes.Structure):
         ("epilogue", ctypes.c_int32), ("batch", ctypes.c_int32),
         ("stride_a", ctypes.c_int64), ("stride_b", ctypes.c_int64),
         ("stride_bias", ctypes.c_int64),
+        ("scale", ctypes.c_double),
     ]
 
 
@@ -52,6 +55,7 @@ class Problem:
     stride_a: int = 0
     stride_b: int = 0
     stride_bias: int = 0
+    scale: float = 1.0
 
     def resolved(self) -> "Problem":
         lda = self.lda or (self.K if self.layout_a == ROW_MAJOR else self.M)
@@ -60,13 +64,13 @@ class Problem:
         sb = self.stride_b or ldb * (self.K if self.layout_b == ROW_MAJOR else self.N)
         return Problem(self.M, self.N, self.K, self.dtype_a, self.dtype_b,
                        self.layout_a, self.layout_b, lda, ldb, self.epilogue,
-                       self.batch, sa, sb, self.stride_bias)
+                       self.batch, sa, sb, self.stride_bias, self.scale)
 
     def _c(self) -> _CProblem:
         r = self.resolved()
         return _CProblem(r.M, r.N, r.K, r.layout_a, r.layout_b, r.lda, r.ldb,
                          r.dtype_a, r.dtype_b, r.epilogue, r.batch,
-                         r.stride_a, r.stride_b, r.stride_bias)
+                         r.stride_a, r.stride_b, r.stride_bias, r.scale)
 
 
 def build(force: bool = False) -> str:
@@ -107,6 +111,10 @@ def _load():
         lib.ref_f32_to_f16_rne.argtypes = [ctypes.c_float]
         lib.ref_activation.restype = ctypes.c_double
         lib.ref_activation.argtypes = [ctypes.c_int, ctypes.c_double]
+        lib.ref_epilogue.restype = ctypes.c_double
+        lib.ref_epilogue.argtypes = [ctypes.c_int, ctypes.c_double, ctypes.c_double]
+        lib.ref_sigmoid.restype = ctypes.c_double
+        lib.ref_sigmoid.argtypes = [ctypes.c_double]
         lib.ref_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -191,6 +199,14 @@ def ref_gemm_points(p: Problem, A, B, bias, pb, pi, pj, want=("y",)):
 
 def activation(epilogue: int, t: float) -> float:
     return _load().ref_activation(epilogue, t)
+
+
+def epilogue(code: int, t: float, scale: float) -> float:
+    return _load().ref_epilogue(code, t, scale)
+
+
+def sigmoid(t: float) -> float:
+    return _load().ref_sigmoid(t)
 
 
 def num_threads() -> int:

@@ -83,7 +83,8 @@ static inline double load_elem(const void* base, int dtype, int64_t idx) {
 
 static int epilogue_has_bias(int e) {
   return e == REF_EPI_BIAS || e == REF_EPI_BIAS_RELU ||
-         e == REF_EPI_BIAS_GELU_ERF || e == REF_EPI_BIAS_GELU_TANH;
+         e == REF_EPI_BIAS_GELU_ERF || e == REF_EPI_BIAS_GELU_TANH ||
+         e == REF_EPI_BIAS_SWISH_SCALE || e == REF_EPI_BIAS_SIGMOID_SCALE_RESIDUAL;
 }
 
 /* act(t).  GELU (erf form) = t * Phi(t) = t/2 * (1 + erf(t/sqrt 2));
@@ -106,13 +107,34 @@ double ref_activation(int epilogue, double t) {
   }
 }
 
+/* sigma(t) = 1 / (1 + exp(-t)); written so that exp never sees a large positive argument. */
+double ref_sigmoid(double t) {
+  if (t >= 0.0) return 1.0 / (1.0 + exp(-t));
+  const double e = exp(t);
+  return e / (1.0 + e);
+}
+
+/* Every epilogue: the ones above, and the two with a scalar scale c. */
+double ref_epilogue(int epilogue, double t, double scale) {
+  switch (epilogue) {
+    case REF_EPI_BIAS_SWISH_SCALE:
+    case REF_EPI_SWISH_SCALE:
+      return scale * (t * ref_sigmoid(t));
+    case REF_EPI_BIAS_SIGMOID_SCALE_RESIDUAL:
+    case REF_EPI_SIGMOID_SCALE_RESIDUAL:
+      return scale * ref_sigmoid(t) + t;
+    default:
+      return ref_activation(epilogue, t);
+  }
+}
+
 /* ---- one output element -------------------------------------------------- */
 
 static int check_problem(const ref_problem_t* p, const void* A, const void* B,
                          const float* bias) {
   if (!p || !A || !B) return -1;
   if (p->M <= 0 || p->N <= 0 || p->K <= 0 || p->batch < 1) return -1;
-  if (p->epilogue < REF_EPI_NONE || p->epilogue > REF_EPI_GELU_ERF) return -1;
+  if (p->epilogue < REF_EPI_NONE || p->epilogue > REF_EPI_SIGMOID_SCALE_RESIDUAL) return -1;
   if (epilogue_has_bias(p->epilogue) != (bias != NULL)) return -1;
   if (p->lda < (p->layout_a == REF_ROW_MAJOR ? p->K : p->M)) return -1;
   if (p->ldb < (p->layout_b == REF_ROW_MAJOR ? p->N : p->K)) return -1;
@@ -138,7 +160,7 @@ static void one_element(const ref_problem_t* p, const void* A, const void* B,
   }
   double tt = z;
   if (bias) tt += (double)bias[b * p->stride_bias + j];
-  if (y) *y = ref_activation(p->epilogue, tt);
+  if (y) *y = ref_epilogue(p->epilogue, tt, p->scale);
   if (t) *t = tt;
   if (s) *s = sabs;
 }

@@ -11,7 +11,15 @@
  *   z[b,i,j] = sum_{k=0}^{K-1} a[b,i,k] * w[b,k,j]          (fp64, k ascending)
  *   s[b,i,j] = sum_k |a[b,i,k] * w[b,k,j]|                   (for error bounds)
  *   t[b,i,j] = z[b,i,j] + bias[b,j]        (if the epilogue has a bias)
- *   y[b,i,j] = act(t[b,i,j])               act in {id, relu, gelu_erf, gelu_tanh}
+ *   y[b,i,j] = act(t[b,i,j])               act in {id, relu, gelu_erf, gelu_tanh,
+ *                                                  swish_scale, sigmoid_scale_residual}
+ *
+ * The last two are the post-ops of the paper's "matmul + Swish + scaling" and "GEMM +
+ * sigmoid + scaling + residual add" tasks (App. "Per-task results").  The paper gives
+ * only the names; they are read here as the element-wise formulas the names spell out,
+ * with sigma(t) = 1 / (1 + exp(-t)) and a scalar scale c:
+ *   swish_scale(t)            = c * t * sigma(t)
+ *   sigmoid_scale_residual(t) = c * sigma(t) + t     (the residual is the GEMM output itself)
  *
  * Every stored operand element (fp32, bf16 or fp16) is converted exactly to
  * fp64 first; products of two such values are exact in fp64.  Outputs stay in
@@ -39,7 +47,11 @@ enum {
   REF_EPI_BIAS_GELU_ERF = 3,
   REF_EPI_BIAS_GELU_TANH = 4,
   REF_EPI_RELU = 5,
-  REF_EPI_GELU_ERF = 6
+  REF_EPI_GELU_ERF = 6,
+  REF_EPI_BIAS_SWISH_SCALE = 7,
+  REF_EPI_BIAS_SIGMOID_SCALE_RESIDUAL = 8,
+  REF_EPI_SWISH_SCALE = 9,
+  REF_EPI_SIGMOID_SCALE_RESIDUAL = 10
 };
 
 typedef struct {
@@ -51,6 +63,7 @@ typedef struct {
   int32_t batch;                   /* >= 1 */
   int64_t stride_a, stride_b;      /* elements between consecutive batches */
   int64_t stride_bias;             /* 0 = one bias shared by all batches */
+  double scale;                    /* the scalar c of the *_SCALE epilogues; ignored by the others */
 } ref_problem_t;
 
 /* Full product.  y, t, s: each either NULL or room for batch*M*N doubles.
@@ -70,7 +83,9 @@ double   ref_bf16_bits_to_double(uint16_t bits);
 double   ref_f16_bits_to_double(uint16_t bits);
 uint16_t ref_f32_to_bf16_rne(float x);   /* round to nearest, ties to even */
 uint16_t ref_f32_to_f16_rne(float x);
-double   ref_activation(int epilogue, double t);
+double   ref_activation(int epilogue, double t);                 /* the epilogues without a scale */
+double   ref_epilogue(int epilogue, double t, double scale);     /* every epilogue */
+double   ref_sigmoid(double t);
 int      ref_num_threads(void);
 
 #ifdef __cplusplus

@@ -224,6 +224,79 @@ def test_relu_and_identity(oracle):
         assert oracle.activation(e, -3.5) == -3.5
 
 
+def test_sigmoid_point_values_and_identities(oracle):
+    """sigma(ln 3) = 3/4, sigma(-ln 3) = 1/4, sigma(0) = 1/2; sigma(t) + sigma(-t) = 1;
+    sigma(t) = (1 + tanh(t/2)) / 2 (library tanh); tails do not overflow."""
+    assert abs(oracle.sigmoid(math.log(3.0)) - 0.75) < 1e-16
+    assert abs(oracle.sigmoid(-math.log(3.0)) - 0.25) < 1e-16
+    assert oracle.sigmoid(0.0) == 0.5
+    for t in np.linspace(-30, 30, 121):
+        assert abs(oracle.sigmoid(t) + oracle.sigmoid(-t) - 1.0) < 1e-15
+        assert abs(oracle.sigmoid(t) - 0.5 * (1.0 + math.tanh(0.5 * t))) < 1e-15
+    assert oracle.sigmoid(800.0) == 1.0 and oracle.sigmoid(-800.0) == 0.0
+    assert abs(oracle.sigmoid(-50.0) / math.exp(-50.0) - 1.0) < 1e-15
+
+
+def test_swish_scale_and_sigmoid_scale_residual(oracle):
+    """swish_scale(t) = c t sigma(t); sigmoid_scale_residual(t) = c sigma(t) + t.
+    Worked values at t = +-ln 3 and 0, the odd / even part identities
+    (swish(t) - swish(-t) = c t; ssr(t) + ssr(-t) = c), linearity in c, and the
+    large-|t| limits.  A scale applied before the sigmoid, a missing residual or a
+    residual that is scaled too would fail one of these."""
+    ln3 = math.log(3.0)
+    for sw, sr in ((oracle.EPI_SWISH_SCALE, oracle.EPI_SIGMOID_SCALE_RESIDUAL),
+                   (oracle.EPI_BIAS_SWISH_SCALE, oracle.EPI_BIAS_SIGMOID_SCALE_RESIDUAL)):
+        assert abs(oracle.epilogue(sw, ln3, 2.0) - 1.5 * ln3) < 1e-15
+        assert abs(oracle.epilogue(sw, -ln3, 2.0) + 0.5 * ln3) < 1e-15
+        assert oracle.epilogue(sw, 0.0, 7.0) == 0.0
+        assert abs(oracle.epilogue(sr, ln3, 2.0) - (1.5 + ln3)) < 1e-15
+        assert abs(oracle.epilogue(sr, -ln3, 2.0) - (0.5 - ln3)) < 1e-15
+        assert oracle.epilogue(sr, 0.0, 7.0) == 3.5
+        for t in np.linspace(-12, 12, 49):
+            for c in (0.5, 1.0, -3.0):
+                assert abs(oracle.epilogue(sw, t, c) - oracle.epilogue(sw, -t, c) - c * t) < 1e-13
+                assert abs(oracle.epilogue(sr, t, c) + oracle.epilogue(sr, -t, c) - c) < 1e-13
+                assert abs(oracle.epilogue(sw, t, c) - c * oracle.epilogue(sw, t, 1.0)) < 1e-13
+                assert abs(oracle.epilogue(sr, t, c) - t - c * (oracle.epilogue(sr, t, 1.0) - t)) < 1e-13
+            # scale 0 kills swish and leaves the residual alone
+            assert oracle.epilogue(sw, t, 0.0) == 0.0 and oracle.epilogue(sr, t, 0.0) == t
+        assert abs(oracle.epilogue(sw, 40.0, 1.5) - 60.0) < 1e-12
+        assert abs(oracle.epilogue(sw, -40.0, 1.5)) < 1e-15
+        assert abs(oracle.epilogue(sr, 40.0, 1.5) - 41.5) < 1e-12
+        assert abs(oracle.epilogue(sr, -40.0, 1.5) + 40.0) < 1e-12
+    # the older epilogues ignore the scale
+    assert oracle.epilogue(oracle.EPI_RELU, 2.25, 9.0) == 2.25
+    assert oracle.epilogue(oracle.EPI_BIAS, -1.5, 9.0) == -1.5
+
+
+def test_scaled_epilogues_inside_the_product(oracle):
+    """Through ref_gemm: all-ones operands give t = K + bias[j]; the output is the scalar
+    formula of t, with the problem's scale, for every element."""
+    M, N, K = 3, 5, 4
+    bias = np.array([-6, -4.5, -4, -3, 0], dtype=np.float32)       # t = -2, -0.5, 0, 1, 4
+    ones_a = np.full(M * K, 0x3F80, dtype=np.uint16)
+    ones_b = np.full(N * K, 0x3F80, dtype=np.uint16)
+    t = K + bias.astype(np.float64)
+    sig = 0.5 * (1.0 + np.tanh(0.5 * t))
+    p = oracle.Problem(M, N, K, epilogue=oracle.EPI_BIAS_SWISH_SCALE, scale=2.5)
+    out = oracle.ref_gemm(p, ones_a, ones_b, bias, want=("y", "t"))
+    assert np.array_equal(out["t"][0], np.tile(t, (M, 1)))
+    assert np.allclose(out["y"][0], np.tile(2.5 * t * sig, (M, 1)), rtol=0, atol=1e-15)
+    p = oracle.Problem(M, N, K, epilogue=oracle.EPI_BIAS_SIGMOID_SCALE_RESIDUAL, scale=-0.75)
+    y = oracle.ref_gemm(p, ones_a, ones_b, bias)["y"][0]
+    assert np.allclose(y, np.tile(-0.75 * sig + t, (M, 1)), rtol=0, atol=1e-15)
+    p = oracle.Problem(M, N, K, epilogue=oracle.EPI_SWISH_SCALE, scale=2.0)
+    y = oracle.ref_gemm(p, ones_a, ones_b)["y"][0]
+    assert np.allclose(y, 2.0 * K * 0.5 * (1.0 + math.tanh(0.5 * K)), rtol=0, atol=1e-15)
+    pts = oracle.ref_gemm_points(oracle.Problem(M, N, K, epilogue=oracle.EPI_SIGMOID_SCALE_RESIDUAL, scale=3.0),
+                                 ones_a, ones_b, None, [0, 0], [0, 2], [1, 4])["y"]
+    assert np.allclose(pts, 3.0 * 0.5 * (1.0 + math.tanh(0.5 * K)) + K, rtol=0, atol=1e-15)
+    with pytest.raises(ValueError):
+        oracle.ref_gemm(oracle.Problem(M, N, K, epilogue=oracle.EPI_BIAS_SWISH_SCALE), ones_a, ones_b, None)
+    with pytest.raises(ValueError):
+        oracle.ref_gemm(oracle.Problem(M, N, K, epilogue=oracle.EPI_SWISH_SCALE), ones_a, ones_b, bias)
+
+
 def test_bias_is_per_column_added_once_before_activation(oracle):
     """A = 0 -> C[i,j] = act(bias[j]); all-ones -> K + bias[j].  Catches a
     per-row bias, a bias added after the activation or twice."""
