@@ -80,7 +80,8 @@ def gpu_desc(g, w):
     dt = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16}
     lay = {"row": g.ROW_MAJOR, "col": g.COL_MAJOR}
     return g.GemmDesc(w.M, w.N, w.K, dtype=dt[w.dtype], layout_a=lay[w.layout_a],
-                      layout_b=lay[w.layout_b], epilogue=g.EPILOGUES[w.epilogue], batch=w.batch)
+                      layout_b=lay[w.layout_b], epilogue=g.EPILOGUES[w.epilogue], batch=w.batch,
+                      scale=w.scale)
 
 
 def cpu_baseline(w, A, B, bias, target_s, gpu_out):
@@ -93,11 +94,15 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
     lay = {"row": oracle.ROW_MAJOR, "col": oracle.COL_MAJOR}
     epi = {"none": oracle.EPI_NONE, "bias": oracle.EPI_BIAS, "bias_relu": oracle.EPI_BIAS_RELU,
            "bias_gelu_erf": oracle.EPI_BIAS_GELU_ERF, "bias_gelu_tanh": oracle.EPI_BIAS_GELU_TANH,
-           "relu": oracle.EPI_RELU, "gelu_erf": oracle.EPI_GELU_ERF}
+           "relu": oracle.EPI_RELU, "gelu_erf": oracle.EPI_GELU_ERF,
+           "bias_swish_scale": oracle.EPI_BIAS_SWISH_SCALE,
+           "bias_sigmoid_scale_residual": oracle.EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
+           "swish_scale": oracle.EPI_SWISH_SCALE,
+           "sigmoid_scale_residual": oracle.EPI_SIGMOID_SCALE_RESIDUAL}
 
     def oracle_problem(o, x):
         return o.Problem(x.M, x.N, x.K, dt[x.dtype], dt[x.dtype], lay[x.layout_a], lay[x.layout_b],
-                         epilogue=epi[x.epilogue], batch=x.batch)
+                         epilogue=epi[x.epilogue], batch=x.batch, scale=x.scale)
 
     a, b = wl.storage_numpy(A), wl.storage_numpy(B)
     bz = None if bias is None else bias.numpy()

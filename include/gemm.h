@@ -35,7 +35,13 @@ typedef enum { GEMM_ROW_MAJOR = 0, GEMM_COL_MAJOR = 1 } gemm_layout_t;
 /* Epilogues.  bias is a length-N fp32 vector added to every row (one value per
  * output column), before the activation.
  *   GELU_ERF (t) = t/2 * (1 + erf(t / sqrt 2))
- *   GELU_TANH(t) = t/2 * (1 + tanh(sqrt(2/pi) * (t + 0.044715 t^3)))          */
+ *   GELU_TANH(t) = t/2 * (1 + tanh(sqrt(2/pi) * (t + 0.044715 t^3)))
+ * The last four are the post-ops of the paper's "matmul + Swish + scaling" and "GEMM +
+ * sigmoid + scaling + residual add" tasks (App. "Per-task results"), read as the
+ * element-wise formulas their names spell out, with sigma(t) = 1 / (1 + exp(-t)) and
+ * c = gemm_desc_t.scale:
+ *   SWISH_SCALE(t)            = c * t * sigma(t)
+ *   SIGMOID_SCALE_RESIDUAL(t) = c * sigma(t) + t     (the residual is the GEMM output itself) */
 typedef enum {
   GEMM_EPI_NONE = 0,
   GEMM_EPI_BIAS = 1,
@@ -43,7 +49,11 @@ typedef enum {
   GEMM_EPI_BIAS_GELU_ERF = 3,
   GEMM_EPI_BIAS_GELU_TANH = 4,
   GEMM_EPI_RELU = 5,
-  GEMM_EPI_GELU_ERF = 6
+  GEMM_EPI_GELU_ERF = 6,
+  GEMM_EPI_BIAS_SWISH_SCALE = 7,
+  GEMM_EPI_BIAS_SIGMOID_SCALE_RESIDUAL = 8,
+  GEMM_EPI_SWISH_SCALE = 9,
+  GEMM_EPI_SIGMOID_SCALE_RESIDUAL = 10
 } gemm_epilogue_t;
 
 /* Status codes: 0 is success, every failure is negative. */
@@ -57,7 +67,8 @@ enum {
   GEMM_ERR_NO_DEVICE = -6,    /* current device is not a gfx950 GPU */
   GEMM_ERR_LAUNCH = -7,       /* the HIP runtime refused the launch */
   GEMM_ERR_BAD_ENUM = -8,     /* an enum field holds a value outside its range */
-  GEMM_ERR_BAD_CONFIG = -9    /* tile configuration index unknown or not applicable */
+  GEMM_ERR_BAD_CONFIG = -9,   /* tile configuration index unknown or not applicable */
+  GEMM_ERR_BAD_SCALE = -10    /* a *_SCALE epilogue with a scale that is not finite */
 };
 
 /*
@@ -81,6 +92,7 @@ typedef struct {
   int32_t epilogue;                              /* gemm_epilogue_t */
   int32_t batch;                                 /* >= 1 */
   int64_t stride_a, stride_b, stride_c, stride_bias;
+  float scale;                                   /* c of the *_SCALE epilogues (finite); ignored by the others */
 } gemm_desc_t;
 
 /*

@@ -4,7 +4,8 @@ this package only marshals arguments."""
 from .binding import (  # noqa: F401
     F32, BF16, F16, ROW_MAJOR, COL_MAJOR,
     EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
-    EPI_RELU, EPI_GELU_ERF, EPILOGUES,
+    EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
+    EPI_SWISH_SCALE, EPI_SIGMOID_SCALE_RESIDUAL, EPILOGUES,
     GemmError, GemmDesc, Plan,
     gemm_create, gemm_create_config, gemm_run, gemm_tune, gemm_destroy, gemm_status_string,
     gemm_plan_info, gemm_config_count, gemm_config_name, config_names, library_path, load_library,

@@ -15,10 +15,15 @@ _LIB_PATH = os.path.join(HERE, "libmi355gemm.so")
 F32, BF16, F16 = 0, 1, 2
 ROW_MAJOR, COL_MAJOR = 0, 1
 (EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
- EPI_RELU, EPI_GELU_ERF) = range(7)
+ EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
+ EPI_SWISH_SCALE, EPI_SIGMOID_SCALE_RESIDUAL) = range(11)
 EPILOGUES = {"none": EPI_NONE, "bias": EPI_BIAS, "bias_relu": EPI_BIAS_RELU,
              "bias_gelu_erf": EPI_BIAS_GELU_ERF, "bias_gelu_tanh": EPI_BIAS_GELU_TANH,
-             "relu": EPI_RELU, "gelu_erf": EPI_GELU_ERF}
+             "relu": EPI_RELU, "gelu_erf": EPI_GELU_ERF,
+             "bias_swish_scale": EPI_BIAS_SWISH_SCALE,
+             "bias_sigmoid_scale_residual": EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
+             "swish_scale": EPI_SWISH_SCALE,
+             "sigmoid_scale_residual": EPI_SIGMOID_SCALE_RESIDUAL}
 
 GEMM_OK = 0
 
@@ -40,16 +45,17 @@ class GemmDesc(ctypes.Structure):
         ("epilogue", ctypes.c_int32), ("batch", ctypes.c_int32),
         ("stride_a", ctypes.c_int64), ("stride_b", ctypes.c_int64), ("stride_c", ctypes.c_int64),
         ("stride_bias", ctypes.c_int64),
+        ("scale", ctypes.c_float),
     ]
 
     def __init__(self, M=0, N=0, K=0, dtype=BF16, layout_a=ROW_MAJOR, layout_b=COL_MAJOR,
                  layout_c=ROW_MAJOR, lda=0, ldb=0, ldc=0, dtype_c=None, epilogue=EPI_NONE,
                  batch=1, stride_a=0, stride_b=0, stride_c=0, stride_bias=0,
-                 dtype_b=None, dtype_bias=F32):
+                 dtype_b=None, dtype_bias=F32, scale=1.0):
         super().__init__(M, N, K, layout_a, layout_b, layout_c, lda, ldb, ldc,
                          dtype, dtype if dtype_b is None else dtype_b,
                          dtype if dtype_c is None else dtype_c, dtype_bias,
-                         epilogue, batch, stride_a, stride_b, stride_c, stride_bias)
+                         epilogue, batch, stride_a, stride_b, stride_c, stride_bias, scale)
 
 
 _lib = None

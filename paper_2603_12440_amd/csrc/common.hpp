@@ -25,21 +25,32 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 // Epilogue codes: numerically equal to gemm_epilogue_t in the public header.
 enum : int {
   kEpiNone = 0, kEpiBias = 1, kEpiBiasRelu = 2, kEpiBiasGeluErf = 3,
-  kEpiBiasGeluTanh = 4, kEpiRelu = 5, kEpiGeluErf = 6
+  kEpiBiasGeluTanh = 4, kEpiRelu = 5, kEpiGeluErf = 6,
+  kEpiBiasSwishScale = 7, kEpiBiasSigmoidScaleResidual = 8,
+  kEpiSwishScale = 9, kEpiSigmoidScaleResidual = 10
 };
 
 __host__ __device__ inline bool epilogue_has_bias(int e) {
-  return e >= kEpiBias && e <= kEpiBiasGeluTanh;
+  return (e >= kEpiBias && e <= kEpiBiasGeluTanh) || e == kEpiBiasSwishScale ||
+         e == kEpiBiasSigmoidScaleResidual;
+}
+__host__ __device__ inline bool epilogue_has_scale(int e) {
+  return e >= kEpiBiasSwishScale && e <= kEpiSigmoidScaleResidual;
 }
 
 // Activation kinds after the bias has been folded away.
-enum : int { kActNone = 0, kActRelu = 1, kActGeluErf = 2, kActGeluTanh = 3 };
+enum : int {
+  kActNone = 0, kActRelu = 1, kActGeluErf = 2, kActGeluTanh = 3,
+  kActSwishScale = 4, kActSigmoidScaleResidual = 5
+};
 
 __host__ __device__ inline int epilogue_activation(int e) {
   switch (e) {
     case kEpiBiasRelu: case kEpiRelu: return kActRelu;
     case kEpiBiasGeluErf: case kEpiGeluErf: return kActGeluErf;
     case kEpiBiasGeluTanh: return kActGeluTanh;
+    case kEpiBiasSwishScale: case kEpiSwishScale: return kActSwishScale;
+    case kEpiBiasSigmoidScaleResidual: case kEpiSigmoidScaleResidual: return kActSigmoidScaleResidual;
     default: return kActNone;
   }
 }
@@ -72,12 +83,26 @@ __device__ __forceinline__ float gelu_tanh_f32(float t) {
   return 0.5f * t * one_plus_tanh;
 }
 
-// act(t) in fp32.  `act` is uniform over the launch.
-__device__ __forceinline__ float apply_activation(int act, float t) {
+// sigma(t) = 1 / (1 + exp(-t)) with the hardware exp2 and reciprocal.  exp2 overflows to
+// +inf for t below about -88, whose reciprocal is the correct limit 0.
+__device__ __forceinline__ float sigmoid_f32(float t) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t));
+}
+// The post-ops of the paper's "matmul + Swish + scaling" and "GEMM + sigmoid + scaling +
+// residual add" tasks (App. "Per-task results"); c is the descriptor's scale.
+__device__ __forceinline__ float swish_scale_f32(float t, float c) { return c * (t * sigmoid_f32(t)); }
+__device__ __forceinline__ float sigmoid_scale_residual_f32(float t, float c) {
+  return fmaf(c, sigmoid_f32(t), t);
+}
+
+// act(t) in fp32.  `act` and `scale` are uniform over the launch.
+__device__ __forceinline__ float apply_activation(int act, float t, float scale) {
   switch (act) {
     case kActRelu: return fmaxf(t, 0.0f);
     case kActGeluErf: return gelu_erf_f32(t);
     case kActGeluTanh: return gelu_tanh_f32(t);
+    case kActSwishScale: return swish_scale_f32(t, scale);
+    case kActSigmoidScaleResidual: return sigmoid_scale_residual_f32(t, scale);
     default: return t;
   }
 }

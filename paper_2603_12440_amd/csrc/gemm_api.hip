@@ -9,6 +9,7 @@
 
 #include <atomic>
 #include <cstdio>
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -77,6 +78,7 @@ hipError_t launch_simt_typed(const gemm_plan& pl, const void* A, const void* B, 
   a.stride_bias = d.stride_bias;
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
+  a.scale = d.scale;
   simt_gemm_kernel<TIn, TOut, TM, TN, TK><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
@@ -101,6 +103,7 @@ hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* 
   a.stride_bias = d.stride_bias;
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
+  a.scale = d.scale;
   a.c_f32 = d.dtype_c == GEMM_F32;
   a.tiles_m = (int)((d.M + BM - 1) / BM);
   a.tiles_n = (int)((d.N + BN - 1) / BN);
@@ -122,6 +125,7 @@ hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void
   a.stride_bias = d.stride_bias;
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
+  a.scale = d.scale;
   a.y_f32 = d.dtype_c == GEMM_F32;
   skinny_gemm_kernel<T, MB, WAVES><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
@@ -139,6 +143,7 @@ hipError_t launch_skinny_mfma(const gemm_plan& pl, const void* A, const void* B,
   a.stride_bias = d.stride_bias;
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
+  a.scale = d.scale;
   a.y_f32 = d.dtype_c == GEMM_F32;
   skinny_mfma_kernel<T, RB, UNROLL><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
@@ -156,6 +161,7 @@ hipError_t launch_skinny_ring(const gemm_plan& pl, const void* A, const void* B,
   a.stride_bias = d.stride_bias;
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
+  a.scale = d.scale;
   a.y_f32 = d.dtype_c == GEMM_F32;
   skinny_ring_kernel<T, NS><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
@@ -173,6 +179,7 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
   a.stride_bias = d.stride_bias;
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
+  a.scale = d.scale;
   a.y_f32 = d.dtype_c == GEMM_F32;
   skinny_stage_kernel<T, DEPTH, RB><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
@@ -248,8 +255,13 @@ int resolve(const gemm_desc_t* in, gemm_desc_t* out) {
   gemm_desc_t d = *in;
   if (!in_range(d.layout_a, 0, 1) || !in_range(d.layout_b, 0, 1) || !in_range(d.layout_c, 0, 1) ||
       !in_range(d.dtype_a, 0, 2) || !in_range(d.dtype_b, 0, 2) || !in_range(d.dtype_c, 0, 2) ||
-      !in_range(d.dtype_bias, 0, 2) || !in_range(d.epilogue, 0, GEMM_EPI_GELU_ERF))
+      !in_range(d.dtype_bias, 0, 2) || !in_range(d.epilogue, 0, GEMM_EPI_SIGMOID_SCALE_RESIDUAL))
     return GEMM_ERR_BAD_ENUM;
+  if (epilogue_has_scale(d.epilogue)) {
+    if (!std::isfinite(d.scale)) return GEMM_ERR_BAD_SCALE;
+  } else {
+    d.scale = 1.0f;                              // ignored: keep the plan's copy tidy
+  }
   if (d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch < 1) return GEMM_ERR_BAD_DIM;
   const int64_t kMaxDim = (int64_t)1 << 30;
   if (d.M > kMaxDim || d.N > kMaxDim || d.K > kMaxDim || d.batch > 65535) return GEMM_ERR_BAD_DIM;
@@ -624,6 +636,7 @@ const char* gemm_status_string(int status) {
     case GEMM_ERR_LAUNCH: return "kernel launch failed";
     case GEMM_ERR_BAD_ENUM: return "enum value out of range";
     case GEMM_ERR_BAD_CONFIG: return "tile configuration unknown or not applicable";
+    case GEMM_ERR_BAD_SCALE: return "epilogue scale is not finite";
     default: return "unknown status";
   }
 }

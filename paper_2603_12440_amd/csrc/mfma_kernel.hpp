@@ -25,6 +25,7 @@ struct MfmaArgs {
   int64_t lda, ldb, ldc;                               // elements
   int64_t stride_a, stride_b, stride_c, stride_bias;   // elements between batches
   int has_bias, act, c_f32;
+  float scale;                 // scalar of the *_scale activations
   int tiles_m, tiles_n;        // ceil(M/BM), ceil(N/BN)
   int group_m;                 // tile rows per scheduling group
   int xcd_remap;               // 1: spread consecutive tile ids within one XCD
@@ -501,6 +502,8 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     case kActRelu: drain([](float t) { return fmaxf(t, 0.0f); }); break;
     case kActGeluErf: drain([](float t) { return gelu_erf_f32(t); }); break;
     case kActGeluTanh: drain([](float t) { return gelu_tanh_f32(t); }); break;
+    case kActSwishScale: { const float c = p.scale; drain([c](float t) { return swish_scale_f32(t, c); }); } break;
+    case kActSigmoidScaleResidual: { const float c = p.scale; drain([c](float t) { return sigmoid_scale_residual_f32(t, c); }); } break;
     default: drain([](float t) { return t; }); break;
   }
   if (!through_lds) return;

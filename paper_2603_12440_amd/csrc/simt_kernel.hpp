@@ -21,6 +21,7 @@ struct SimtArgs {
   int64_t c_si, c_sj;          // element strides of C along i and j
   int64_t stride_a, stride_b, stride_c, stride_bias;  // batch strides
   int has_bias, act;
+  float scale;                 // scalar of the *_scale activations
 };
 
 template <typename TIn, typename TOut, int TM, int TN, int TK>
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(256) void simt_gemm_kernel(SimtArgs p) {
       if (j >= p.N) continue;
       float t = acc[r][c];
       if (bias) t += bias[j];
-      C[i * p.c_si + j * p.c_sj] = from_float<TOut>(apply_activation(p.act, t));
+      C[i * p.c_si + j * p.c_sj] = from_float<TOut>(apply_activation(p.act, t, p.scale));
     }
   }
 }

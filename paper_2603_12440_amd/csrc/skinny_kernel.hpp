@@ -23,6 +23,7 @@ struct SkinnyArgs {
   int64_t ldx, ldw, ldy;                                // elements
   int64_t stride_x, stride_w, stride_y, stride_bias;    // elements between batches
   int has_bias, act, y_f32;
+  float scale;                 // scalar of the *_scale activations
 };
 
 // Sum over the 64 lanes of a wavefront; every lane gets the total.
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
       if (m >= p.M) continue;
       float v = t[m];
       if (bias) v += bias[n];
-      v = apply_activation(p.act, v);
+      v = apply_activation(p.act, v, p.scale);
       const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
       if (p.y_f32) ((float*)p.Y)[o] = v;
       else ((T*)p.Y)[o] = from_float<T>(v);
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(256) void skinny_mfma_kernel(SkinnyArgs p) {
           for (int e = 0; e < 4; ++e) {
             const int m = oct * 4 + e;
             if (m < p.M) {
-              const float v = apply_activation(p.act, t[e] + bv);
+              const float v = apply_activation(p.act, t[e] + bv, p.scale);
               const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
               if (p.y_f32) ((float*)p.Y)[o] = v;
               else ((T*)p.Y)[o] = from_float<T>(v);
@@ -476,7 +477,7 @@ __global__ __launch_bounds__(256) void skinny_ring_kernel(SkinnyArgs p) {
                     red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
     const int m = 8 * wave + 4 * fh + e;
     if (m < p.M && n < p.N) {
-      const float v = apply_activation(p.act, t + bv);
+      const float v = apply_activation(p.act, t + bv, p.scale);
       const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
       if (p.y_f32) ((float*)p.Y)[o] = v;
       else ((T*)p.Y)[o] = from_float<T>(v);
@@ -640,7 +641,7 @@ __global__ __launch_bounds__(256) void skinny_stage_kernel(SkinnyArgs p) {
                     red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
     const int m = 8 * wave + 4 * fh + e;
     if (m < p.M && n < p.N) {
-      const float v = apply_activation(p.act, t + bv);
+      const float v = apply_activation(p.act, t + bv, p.scale);
       const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
       if (p.y_f32) ((float*)p.Y)[o] = v;
       else ((T*)p.Y)[o] = from_float<T>(v);

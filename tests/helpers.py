@@ -25,13 +25,17 @@ def oracle_codes(o):
             {"row": o.ROW_MAJOR, "col": o.COL_MAJOR},
             {"none": o.EPI_NONE, "bias": o.EPI_BIAS, "bias_relu": o.EPI_BIAS_RELU,
              "bias_gelu_erf": o.EPI_BIAS_GELU_ERF, "bias_gelu_tanh": o.EPI_BIAS_GELU_TANH,
-             "relu": o.EPI_RELU, "gelu_erf": o.EPI_GELU_ERF})
+             "relu": o.EPI_RELU, "gelu_erf": o.EPI_GELU_ERF,
+             "bias_swish_scale": o.EPI_BIAS_SWISH_SCALE,
+             "bias_sigmoid_scale_residual": o.EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
+             "swish_scale": o.EPI_SWISH_SCALE,
+             "sigmoid_scale_residual": o.EPI_SIGMOID_SCALE_RESIDUAL})
 
 
 def oracle_problem(o, w: wl.Workload, lda=0, ldb=0, stride_a=0, stride_b=0, stride_bias=0):
     dt, lay, epi = oracle_codes(o)
     return o.Problem(w.M, w.N, w.K, dt[w.dtype], dt[w.dtype], lay[w.layout_a], lay[w.layout_b],
-                     lda, ldb, epi[w.epilogue], w.batch, stride_a, stride_b, stride_bias)
+                     lda, ldb, epi[w.epilogue], w.batch, stride_a, stride_b, stride_bias, w.scale)
 
 
 def gpu_desc(g, w: wl.Workload, out_dtype=None, layout_c="row", lda=0, ldb=0, ldc=0,
@@ -42,7 +46,7 @@ def gpu_desc(g, w: wl.Workload, out_dtype=None, layout_c="row", lda=0, ldb=0, ld
                       layout_b=lay[w.layout_b], layout_c=lay[layout_c], lda=lda, ldb=ldb, ldc=ldc,
                       dtype_c=dt[out_dtype or w.dtype], epilogue=g.EPILOGUES[w.epilogue],
                       batch=w.batch, stride_a=stride_a, stride_b=stride_b, stride_c=stride_c,
-                      stride_bias=stride_bias)
+                      stride_bias=stride_bias, scale=w.scale)
 
 
 def pad_minor(t: torch.Tensor, pad: int, fill=float("nan")) -> torch.Tensor:
@@ -96,9 +100,20 @@ def run_oracle(o, w: wl.Workload, A, B, bias, want=("y", "t", "s"), stride_bias=
 def e2_bound(w: wl.Workload, ref, out_dtype=None):
     """Per-element bound on |C - y| that any summation order in fp32 satisfies."""
     y, t, s = ref["y"], ref["t"], ref["s"]
-    lip = 1.13 if "gelu" in w.epilogue else 1.0
+    # Lipschitz constant of the activation (how an error of t shows in y) and the size of
+    # the terms its fp32 evaluation rounds: |d/dt c t sigma(t)| <= 1.1 |c|,
+    # |d/dt (c sigma(t) + t)| <= 1 + |c|/4.
+    c = abs(w.scale)
+    if "gelu" in w.epilogue:
+        lip, mag = 1.13, 1.0
+    elif "swish_scale" in w.epilogue:
+        lip, mag = 1.1 * c, max(c, 1.0)
+    elif "sigmoid_scale_residual" in w.epilogue:
+        lip, mag = 1.0 + 0.25 * c, max(c, 1.0)
+    else:
+        lip, mag = 1.0, 1.0
     acc = w.K * U32 * s
-    epi = 16 * U32 * (np.abs(t) + 1.0) if w.epilogue != "none" else 0.0
+    epi = 16 * U32 * mag * (np.abs(t) + 1.0) if w.epilogue != "none" else 0.0
     rnd = OUT_ROUNDOFF[out_dtype or w.dtype] * (np.abs(y) + lip * acc + epi) * 1.001
     return lip * acc + epi + rnd + 1e-30
 
@@ -111,6 +126,8 @@ def compare(w: wl.Workload, C: torch.Tensor, ref, A, B, bias, out_dtype=None):
     scale = w.K * float(A.abs().max()) * float(B.abs().max())
     if bias is not None:
         scale += float(bias.abs().max())
+    if "scale" in w.epilogue:
+        scale = scale * max(abs(w.scale), 1.0) + abs(w.scale)
     res = {"e1": float(err.max() / scale), "finite": bool(np.isfinite(c).all())}
     if "s" in ref:
         bound = e2_bound(w, {k: v.reshape(c.shape) for k, v in ref.items()}, out_dtype)

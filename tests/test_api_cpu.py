@@ -60,7 +60,15 @@ def test_descriptor_validation(g):
     assert _status(g, **ok, dtype=g.BF16, dtype_b=g.F16) == -4
     assert _status(g, **ok, dtype=g.F32, dtype_c=g.BF16) == -4
     assert _status(g, **ok, dtype_bias=g.BF16) == -4
-    assert _status(g, **ok, epilogue=7) == -8
+    assert _status(g, **ok, epilogue=11) == -8
+    assert _status(g, **ok, epilogue=-1) == -8
+    # the scale is checked exactly where an epilogue uses it
+    for e in (g.EPI_SWISH_SCALE, g.EPI_SIGMOID_SCALE_RESIDUAL):
+        assert _status(g, **ok, epilogue=e, scale=float("nan")) == -10
+        assert _status(g, **ok, epilogue=e, scale=float("inf")) == -10
+        assert _status(g, **ok, epilogue=e, scale=-2.5) == 0
+    assert _status(g, **ok, epilogue=g.EPI_RELU, scale=float("nan")) == 0
+    assert "scale" in g.gemm_status_string(-10)
     assert _status(g, **ok, layout_a=2) == -8
     assert _status(g, **ok, dtype=3) == -8
     assert _status(g, M=1 << 31, N=64, K=64) == -2

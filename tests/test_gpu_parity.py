@@ -203,7 +203,9 @@ def test_mfma_random_against_oracle(g, oracle, name, changes):
         say("   ", r)
 
 
-@pytest.mark.parametrize("epilogue", ["none", "bias", "bias_relu", "bias_gelu_erf", "bias_gelu_tanh", "relu", "gelu_erf"])
+@pytest.mark.parametrize("epilogue", ["none", "bias", "bias_relu", "bias_gelu_erf", "bias_gelu_tanh", "relu", "gelu_erf",
+                                      "bias_swish_scale", "bias_sigmoid_scale_residual", "swish_scale",
+                                      "sigmoid_scale_residual"])
 def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
     for (M, N, K, cfg) in [(260, 264, 136, "mfma_256x256x64_w2x2_s2"), (130, 140, 72, "mfma_128x128x64_w2x2_s2"),
                            (3, 515, 264, "skinny_m4_w4_g1"), (8, 100, 1032, "skinny_m8_w4_g1"),
@@ -214,13 +216,46 @@ def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
                            (70, 90, 50, "simt_64x64x16")]:
         # pre-activations of order 1 so that the activations' curved parts are exercised
         w = wl.Workload("t", M, N, K, dist_a=("normal", 1.0), dist_b=("normal", 1.5 / np.sqrt(K)),
-                        epilogue=epilogue, dist_bias=("uniform", 1.0), seed_a=11, seed_b=12, seed_bias=13)
+                        epilogue=epilogue, dist_bias=("uniform", 1.0), seed_a=11, seed_b=12, seed_bias=13,
+                        scale=-1.75 if "residual" in epilogue else 2.5)
         A, B, bias = wl.make_inputs(w)
         ref = run_oracle(oracle, w, A, B, bias)
         for od in (None, "f32"):
             say(f"epilogue {epilogue} {cfg} out={od}")
             C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg), out_dtype=od)
             assert_parity(w, C, ref, A, B, bias, out_dtype=od)
+
+
+def test_scaled_epilogues_closed_form_and_tails(g, oracle):
+    """A = one-hot (k = 0), B row 0 = chosen pre-activations t_j (exact in bf16): C[i, j] is the
+    scalar formula of t_j.  The t_j include 0, +-ln 3 rounded to bf16, and the far tails where
+    exp overflows in fp32 (sigma -> 0 or 1), for every kernel family, fp32 output."""
+    ts = torch.tensor([0.0, 1.09375, -1.09375, 0.5, -0.5, 8.0, -8.0, 30.0, -30.0, 100.0, -100.0, 200.0,
+                       -200.0, 3.0, -3.0, 0.0078125], dtype=torch.float32)
+    for (M, cfg) in [(40, "mfma_128x128x64_w2x2_s2"), (300, "mfma_256x256x64_w2x4_s2"), (3, "skinny_m4_w4_g1"),
+                     (16, "skinnystage_d2_b512"), (9, "skinnyring_s5"), (33, "simt_32x32x16")]:
+        N, K = 16 * 5, 72
+        for epilogue, c in [("swish_scale", 3.0), ("sigmoid_scale_residual", -0.5)]:
+            w = wl.Workload("t", M, N, K, epilogue=epilogue, scale=c)
+            A = wl.one_hot_columns(M, K, [0]).unsqueeze(0)
+            B = torch.zeros((1, N, K), dtype=torch.bfloat16)
+            B[0, :, 0] = ts.repeat(5).to(torch.bfloat16)
+            say(f"scaled epilogue closed form {epilogue} {cfg}")
+            C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg), out_dtype="f32")
+            t = ts.repeat(5).double().numpy()
+            from scipy.special import expit            # library sigmoid, accurate in both tails
+            sig = expit(t)
+            want = c * t * sig if epilogue == "swish_scale" else c * sig + t
+            got = C[0].double().numpy()
+            assert np.isfinite(got).all(), cfg
+            # fp32 evaluation: a few units of 2^-24 relative (the exponent's argument carries
+            # |t| * 2^-24); tails underflow to exactly 0
+            bad = np.abs(got[0] - want) > 8e-6 * np.abs(want) + 1e-30
+            assert not bad.any(), (cfg, epilogue, t[bad], got[0][bad], want[bad])
+            # rows of a one-hot A are identical
+            assert np.array_equal(got, np.tile(got[0], (M, 1)))
+            ref = run_oracle(oracle, w, A, B, None)
+            assert_parity(w, C, ref, A, B, None, out_dtype="f32")
 
 
 @pytest.mark.parametrize("M", [1, 4, 16])

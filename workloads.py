@@ -39,6 +39,8 @@ class Workload:
     dist_a: Tuple[str, float] = ("normal", 1.0)
     dist_b: Tuple[str, float] = ("normal", 1.0)
     epilogue: str = "none"         # 'none' | 'bias' | 'bias_relu' | 'bias_gelu_erf' | 'bias_gelu_tanh' | 'relu' | 'gelu_erf'
+                                   # | '[bias_]swish_scale' | '[bias_]sigmoid_scale_residual'
+    scale: float = 1.0             # the scalar of the *_scale epilogues
     dist_bias: Tuple[str, float] = ("uniform", 0.1)
     batch: int = 1
     seed_a: int = 1
