@@ -90,6 +90,13 @@ WORKLOADS = {w.name: w for w in [
     Workload("gelu_8192x16384x4096", 8192, 16384, 4096, dist_a=("normal", _k(4096)),
              dist_b=("normal", _k(4096)), epilogue="bias_gelu_erf",
              seed_a=5001, seed_b=5002, seed_bias=5003),
+    # the two scaled post-ops on the same shape
+    Workload("swish_8192x16384x4096", 8192, 16384, 4096, dist_a=("normal", _k(4096)),
+             dist_b=("normal", 1.5 * _k(4096)), epilogue="bias_swish_scale", scale=2.0,
+             dist_bias=("uniform", 1.0), seed_a=5011, seed_b=5012, seed_bias=5013),
+    Workload("sigres_8192x16384x4096", 8192, 16384, 4096, dist_a=("normal", _k(4096)),
+             dist_b=("normal", 1.5 * _k(4096)), epilogue="bias_sigmoid_scale_residual", scale=0.5,
+             dist_bias=("uniform", 1.0), seed_a=5021, seed_b=5022, seed_bias=5023),
     Workload("batched_64x512x512x128", 512, 512, 128, dist_a=("normal", _k(128)),
              dist_b=("normal", _k(128)), batch=64, seed_a=5004, seed_b=5005,
              seed_bias=5006, bound="hbm"),
