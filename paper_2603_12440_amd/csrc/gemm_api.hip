@@ -228,6 +228,7 @@ const Config kConfigs[] = {
     MFMA_CFG(256, 256, 32, 2, 2, 4),
     MFMA_CFG(256, 128, 64, 2, 2, 2),
     MFMA_CFG(128, 128, 64, 2, 2, 2),
+    MFMA_CFG(256, 256, 64, 4, 4, 2),
     SKINNY_CFG(1, 4, 1),
     SKINNY_CFG(2, 4, 1),
     SKINNY_CFG(4, 4, 1),

@@ -178,6 +178,8 @@ struct MfmaTile {
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave block must be a multiple of 32x32");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
   static_assert(NSTAGE >= 2, "the hand-over waits assume at least two stages");
+  static_assert(MT * NT >= MT + NT, "a k-step issues one fragment read behind each MFMA: it needs at least as "
+                                    "many MFMAs as reads (wave blocks of at least 2 x 2 MFMA tiles)");
 };
 
 template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     if (i < p.M && j < p.N) {
       T* c = Cb + (int64_t)i * p.ldc + j;
       if (j + 8 <= p.N) {
-        *(u32x4_t*)c = val;
+        __builtin_nontemporal_store(val, (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
       } else {                                 // ragged right edge: element by element
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
