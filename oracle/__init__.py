@@ -1,4 +1,4 @@
-"""CPU oracle for C = epilogue(A.B).  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for C = epilogue(A.B) and for the rotary positional embedding.  TEST INFRASTRUCTURE ONLY.
 
 Only tests, the smoke check and the bench's CPU-baseline leg may import this
 package.  It shares no code with the GPU library and does not import it.
@@ -8,6 +8,6 @@ from .ref import (  # noqa: F401
     EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
     EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
     EPI_SWISH_SCALE, EPI_SIGMOID_SCALE_RESIDUAL,
-    Problem, build, ref_gemm, ref_gemm_points, activation, epilogue, sigmoid, num_threads,
+    Problem, build, ref_gemm, ref_gemm_points, ref_rope, activation, epilogue, sigmoid, num_threads,
     bf16_bits_to_double, f16_bits_to_double, f32_to_bf16_rne, f32_to_f16_rne,
 )

@@ -14,6 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ref_gemm.c")
+_SRC_ROPE = os.path.join(_HERE, "ref_rope.c")
 _LIB = os.path.join(_HERE, "libref_gemm.so")
 
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
@@ -35,6 +36,16 @@ class _CProblem(ctypes.Structure):
         ("stride_a", ctypes.c_int64), ("stride_b", ctypes.c_int64),
         ("stride_bias", ctypes.c_int64),
         ("scale", ctypes.c_double),
+    ]
+
+
+class _CRope(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int64), ("heads", ctypes.c_int64), ("seq", ctypes.c_int64),
+        ("head_dim", ctypes.c_int64),
+        ("dtype_x", ctypes.c_int32), ("dtype_table", ctypes.c_int32),
+        ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_s", ctypes.c_int64),
+        ("table_stride_b", ctypes.c_int64),
     ]
 
 
@@ -75,12 +86,12 @@ class Problem:
 
 def build(force: bool = False) -> str:
     """Compile ref_gemm.c with gcc (plain -O2, OpenMP, no fast-math)."""
+    deps = [_SRC, _SRC_ROPE, os.path.join(_HERE, "ref_gemm.h"), os.path.join(_HERE, "ref_rope.h")]
     if force or not os.path.exists(_LIB) or \
-            os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
-                                         os.path.getmtime(os.path.join(_HERE, "ref_gemm.h"))):
+            os.path.getmtime(_LIB) < max(os.path.getmtime(d) for d in deps):
         cmd = ["gcc", "-std=c11", "-O2", "-fno-fast-math", "-ffp-contract=off",
                "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, _SRC, _SRC_ROPE, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -116,6 +127,9 @@ def _load():
         lib.ref_sigmoid.restype = ctypes.c_double
         lib.ref_sigmoid.argtypes = [ctypes.c_double]
         lib.ref_num_threads.restype = ctypes.c_int
+        lib.ref_rope.restype = ctypes.c_int
+        lib.ref_rope.argtypes = [ctypes.POINTER(_CRope), ctypes.c_void_p, ctypes.c_void_p,
+                                 ctypes.c_void_p, dp]
         _lib = lib
     return _lib
 
@@ -195,6 +209,28 @@ def ref_gemm_points(p: Problem, A, B, bias, pb, pi, pj, want=("y",)):
     if rc != 0:
         raise ValueError("ref_gemm_points rejected the problem")
     return out
+
+
+def ref_rope(batch, heads, seq, head_dim, x, cos, sin, dtype_x=DTYPE_BF16, dtype_table=DTYPE_F32,
+             stride_b=0, stride_h=0, stride_s=0, table_stride_b=0):
+    """Rotary embedding (rotate-half form) of x, logical shape [batch, heads, seq, head_dim]
+    with element strides (0 = packed in that order); cos, sin: [seq, head_dim] or, with
+    table_stride_b, [batch, seq, head_dim].  Returns float64 [batch, heads, seq, head_dim]."""
+    lib = _load()
+    ss = stride_s or head_dim
+    sh = stride_h or seq * head_dim
+    sb = stride_b or heads * seq * head_dim
+    need = (batch - 1) * sb + (heads - 1) * sh + (seq - 1) * ss + head_dim
+    x = _operand(x, dtype_x, need, "x")
+    tneed = (batch - 1) * table_stride_b + seq * head_dim
+    cos = _operand(cos, dtype_table, tneed, "cos")
+    sin = _operand(sin, dtype_table, tneed, "sin")
+    y = np.empty((batch, heads, seq, head_dim), dtype=np.float64)
+    cp = _CRope(batch, heads, seq, head_dim, dtype_x, dtype_table, sb, sh, ss, table_stride_b)
+    rc = lib.ref_rope(ctypes.byref(cp), _ptr(x), _ptr(cos), _ptr(sin), _dptr(y))
+    if rc != 0:
+        raise ValueError("ref_rope rejected the problem")
+    return y
 
 
 def activation(epilogue: int, t: float) -> float:

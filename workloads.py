@@ -1,4 +1,4 @@
-"""Seeded synthetic inputs for C = epilogue(A.B), shared by the CPU oracle's
+"""Seeded synthetic inputs for C = epilogue(A.B) and for the rotary embedding, shared by the CPU oracle's
 tests and the GPU library's tests / bench.
 
 This module holds no GEMM arithmetic: it only draws random (or structured)
@@ -101,6 +101,68 @@ WORKLOADS = {w.name: w for w in [
              dist_b=("normal", _k(128)), batch=64, seed_a=5004, seed_b=5005,
              seed_bias=5006, bound="hbm"),
 ]}
+
+
+@dataclass(frozen=True)
+class RopeWorkload:
+    """One rotary-embedding problem: query and key tensors of a decoder layer, logical
+    shape [batch, heads, seq, head_dim], stored as the projection leaves them
+    ([batch, seq, heads, head_dim] in memory, i.e. the heads axis is a strided view), and
+    per-position cos / sin tables [seq, head_dim] shared by all batches and heads."""
+    name: str
+    batch: int
+    heads_q: int
+    heads_k: int
+    seq: int
+    head_dim: int
+    dtype: str = "bf16"
+    table_dtype: str = "f32"
+    theta: float = 500000.0        # frequency base of the tables
+    seed_q: int = 7001
+    seed_k: int = 7002
+
+    @property
+    def elements(self) -> int:
+        return self.batch * (self.heads_q + self.heads_k) * self.seq * self.head_dim
+
+    @property
+    def bytes(self) -> float:
+        """Compulsory traffic: every element of q and k read once and written once, the tables once."""
+        e = torch.empty((), dtype=TORCH_DTYPE[self.dtype]).element_size()
+        t = torch.empty((), dtype=TORCH_DTYPE[self.table_dtype]).element_size()
+        return float(2 * e * self.elements + 2 * t * self.seq * self.head_dim)
+
+
+ROPE_WORKLOADS = {w.name: w for w in [
+    # small case the oracle finishes at once
+    RopeWorkload("rope_small", 2, 8, 2, 96, 64),
+    # the layer shape of a 1B-parameter Llama-style decoder (32 query heads, 8 key heads of 64), long batch
+    RopeWorkload("rope_llama1b_b8_s4096", 8, 32, 8, 4096, 64),
+    # 128-wide heads (8B-class layer)
+    RopeWorkload("rope_h32_d128_b4_s4096", 4, 32, 8, 4096, 128),
+]}
+
+
+def rope_tables(seq: int, head_dim: int, theta: float = 500000.0, dtype: str = "f32", offset: int = 0):
+    """cos / sin tables [seq, head_dim] as a language model builds them: angle of position p and
+    pair j is p * theta^(-2j / head_dim), the two halves of a row repeat.  Computed in fp64,
+    stored in `dtype`."""
+    j = np.arange(head_dim // 2, dtype=np.float64)
+    inv = theta ** (-2.0 * j / head_dim)
+    ang = (np.arange(seq, dtype=np.float64)[:, None] + offset) * inv[None, :]
+    ang = np.concatenate([ang, ang], axis=1)
+    dt = TORCH_DTYPE[dtype]
+    return torch.from_numpy(np.cos(ang)).to(dt), torch.from_numpy(np.sin(ang)).to(dt)
+
+
+def make_rope_inputs(w: RopeWorkload):
+    """q, k as host tensors of MEMORY shape [batch, seq, heads, head_dim] (logical [b, h, s, d]
+    is their transpose(1, 2)), N(0,1) entries; cos, sin tables [seq, head_dim]."""
+    dt = TORCH_DTYPE[w.dtype]
+    q = _draw(("normal", 1.0), (w.batch, w.seq, w.heads_q, w.head_dim), w.seed_q).to(dt)
+    k = _draw(("normal", 1.0), (w.batch, w.seq, w.heads_k, w.head_dim), w.seed_k).to(dt)
+    cos, sin = rope_tables(w.seq, w.head_dim, w.theta, w.table_dtype)
+    return q, k, cos, sin
 
 
 def scaled(w: Workload, **changes) -> Workload:
