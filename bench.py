@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="square_8192", choices=sorted(wl.WORKLOADS))
+    ap.add_argument("--workload", default="square_8192", choices=sorted(wl.WORKLOADS) + sorted(wl.ROPE_WORKLOADS))
     ap.add_argument("--config", default=None, help="tile configuration name (default: built-in choice)")
     ap.add_argument("--tune", action="store_true",
                     help="pick the tile configuration with gemm_tune (times every applicable one first)")
@@ -143,6 +143,94 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
                       f"batch 0, fp64 triple loop, {t:.2f} s wall"}
 
 
+def bench_rope(args, g, dev):
+    """A rotary-embedding workload: one step = the query and the key tensor of a layer rotated in
+    one launch (include/rope.h).  HBM-bound: algorithmic bytes = every element read and written once."""
+    w = wl.ROPE_WORKLOADS[args.workload]
+    q, k, cos, sin = wl.make_rope_inputs(w)
+    gd = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16}
+    desc = g.RopeDesc(w.batch, w.seq, w.head_dim, dtype=gd[w.dtype], table_dtype=gd[w.table_dtype])
+    nbuf = min(64, max(2, int(np.ceil(1.2e9 / w.bytes))))          # no reuse out of the last-level cache
+    qd, kd = [q.to(dev) for _ in range(nbuf)], [k.to(dev) for _ in range(nbuf)]
+    qy, ky = [torch.empty_like(t) for t in qd], [torch.empty_like(t) for t in kd]
+    cosd, sind = cos.to(dev), sin.to(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def tensor(x, y, heads):
+        st = (w.seq * heads * w.head_dim, w.head_dim, heads * w.head_dim)     # [b, s, h, d] memory
+        return g.RopeTensor(x, y, heads, st, st)
+    sets = [[tensor(qd[j], qy[j], w.heads_q), tensor(kd[j], ky[j], w.heads_k)] for j in range(nbuf)]
+
+    def step(i):
+        g.rope_apply(desc, sets[i % nbuf], cosd, sind, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    achieved = w.bytes / (kern_ms * 1e-3) / 1e9
+    out = {
+        "metric": "rotary embedding throughput (algorithmic bytes / time)",
+        "value": round(w.bytes / (ms_per_step * 1e-3) / 1e9, 3), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "heads_q": w.heads_q, "heads_k": w.heads_k,
+                   "seq": w.seq, "head_dim": w.head_dim, "storage": w.dtype, "tables": w.table_dtype,
+                   "layout": "[batch, seq, heads, head_dim] memory, rotated as [batch, heads, seq, head_dim]",
+                   "buffers_rotated": nbuf},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 3), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": measured_traffic(w.name)},
+    }
+    ok = True
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        od = {"f32": oracle.DTYPE_F32, "bf16": oracle.DTYPE_BF16, "f16": oracle.DTYPE_F16}
+        # the oracle on a bounded sample: the first P positions of every batch, both tensors
+        per_pos = w.batch * (w.heads_q + w.heads_k) * w.head_dim
+        P = 8
+        t_cal = None
+        for _ in range(2):
+            P = min(w.seq, P)
+            t0 = time.perf_counter()
+            refs = []
+            for x, heads in ((q, w.heads_q), (k, w.heads_k)):
+                xs = x[:, :P].contiguous()
+                refs.append(oracle.ref_rope(w.batch, heads, P, w.head_dim, wl.storage_numpy(xs),
+                                            wl.storage_numpy(cos[:P].contiguous()), wl.storage_numpy(sin[:P].contiguous()),
+                                            dtype_x=od[w.dtype], dtype_table=od[w.table_dtype],
+                                            stride_b=P * heads * w.head_dim, stride_h=w.head_dim,
+                                            stride_s=heads * w.head_dim))
+            t = time.perf_counter() - t0
+            if t_cal is None and P < w.seq:
+                t_cal = t
+                P = int(max(P, min(w.seq, P * args.cpu_seconds / max(t, 1e-6))))
+                continue
+            break
+        j = (args.steps - 1) % nbuf
+        u = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24}[w.dtype]
+        for ref, y in zip(refs, (qy[j], ky[j])):
+            got = wl.to_float64(y[:, :P].cpu().transpose(1, 2))
+            ok = ok and bool(np.all(np.abs(got - ref) <= 1.01 * u * np.abs(ref) + 1e-5))
+        e = 2 if w.dtype != "f32" else 4
+        out["cpu_baseline"] = {"value": round(2 * e * P * per_pos / t / 1e9, 4), "unit": "GB/s", "cores": 1,
+                               "kind": "oracle", "gpu_output_matches_oracle_samples": ok,
+                               "sample": f"first {P} of {w.seq} positions of every batch, query and key "
+                                         f"tensors, fp64 loop, {t:.2f} s wall"}
+    print(json.dumps(out))
+    return 0 if ok else 1
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -156,6 +244,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.workload in wl.ROPE_WORKLOADS:
+        return bench_rope(args, g, dev)
     w = wl.WORKLOADS[args.workload]
     A, B, bias = wl.make_inputs(w)
     desc = gpu_desc(g, w)

@@ -58,6 +58,30 @@ class GemmDesc(ctypes.Structure):
                          epilogue, batch, stride_a, stride_b, stride_c, stride_bias, scale)
 
 
+class RopeDesc(ctypes.Structure):
+    """Mirror of rope_desc_t."""
+    _fields_ = [
+        ("batch", ctypes.c_int64), ("seq", ctypes.c_int64), ("head_dim", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("table_dtype", ctypes.c_int32),
+        ("table_stride_b", ctypes.c_int64),
+    ]
+
+    def __init__(self, batch=0, seq=0, head_dim=0, dtype=BF16, table_dtype=F32, table_stride_b=0):
+        super().__init__(batch, seq, head_dim, dtype, table_dtype, table_stride_b)
+
+
+class RopeTensor(ctypes.Structure):
+    """Mirror of rope_tensor_t; x and y are torch device tensors or raw addresses."""
+    _fields_ = [
+        ("x", ctypes.c_void_p), ("y", ctypes.c_void_p), ("heads", ctypes.c_int64),
+        ("x_stride_b", ctypes.c_int64), ("x_stride_h", ctypes.c_int64), ("x_stride_s", ctypes.c_int64),
+        ("y_stride_b", ctypes.c_int64), ("y_stride_h", ctypes.c_int64), ("y_stride_s", ctypes.c_int64),
+    ]
+
+    def __init__(self, x=None, y=None, heads=0, x_strides=(0, 0, 0), y_strides=(0, 0, 0)):
+        super().__init__(_dev_ptr(x), _dev_ptr(y), heads, *x_strides, *y_strides)
+
+
 _lib = None
 
 
@@ -94,6 +118,9 @@ def load_library():
     lib.gemm_status_string.argtypes = [ctypes.c_int]
     lib.gemm_plan_info.restype = ctypes.c_int
     lib.gemm_plan_info.argtypes = [ctypes.c_void_p, ctypes.c_char_p, ctypes.c_size_t]
+    lib.rope_apply.restype = ctypes.c_int
+    lib.rope_apply.argtypes = [ctypes.POINTER(RopeDesc), ctypes.POINTER(RopeTensor), ctypes.c_int,
+                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -202,3 +229,14 @@ def gemm_config_name(config: int) -> Optional[str]:
 
 def config_names() -> List[str]:
     return [gemm_config_name(i) for i in range(gemm_config_count())]
+
+
+def rope_apply(desc: RopeDesc, tensors, cos, sin, stream: Optional[int] = None) -> None:
+    """Enqueue the rotary embedding of one or two tensors (a list of RopeTensor) that share
+    positions and tables, in one launch.  cos, sin: torch device tensors or raw addresses."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    arr = (RopeTensor * len(tensors))(*tensors)
+    _check(load_library().rope_apply(ctypes.byref(desc), arr, len(tensors), _dev_ptr(cos), _dev_ptr(sin),
+                                     stream or None))

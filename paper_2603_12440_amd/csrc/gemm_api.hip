@@ -18,6 +18,7 @@
 #include "mfma_kernel.hpp"
 #include "simt_kernel.hpp"
 #include "skinny_kernel.hpp"
+#include "device_check.hpp"
 
 using namespace mi355gemm;
 
@@ -446,22 +447,6 @@ int fill_launch_shape(gemm_plan& pl) {
 }
 
 // gfx950 check, once per device.
-std::atomic<int> g_dev_ok[64];   // 0 unknown, 1 ok, -1 not gfx950
-
-int check_device() {
-  int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0) { (void)hipGetLastError(); return GEMM_ERR_NO_DEVICE; }
-  if (dev >= 64) return GEMM_ERR_NO_DEVICE;
-  int st = g_dev_ok[dev].load(std::memory_order_acquire);
-  if (st == 0) {
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_NO_DEVICE; }
-    st = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
-    g_dev_ok[dev].store(st, std::memory_order_release);
-  }
-  return st == 1 ? GEMM_OK : GEMM_ERR_NO_DEVICE;
-}
-
 }  // namespace
 
 // ---- C ABI -------------------------------------------------------------------------------
@@ -539,7 +524,7 @@ int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, con
   if (((uintptr_t)A & in_mask) || ((uintptr_t)B & in_mask) ||
       ((uintptr_t)C & ((uintptr_t)esize(d.dtype_c) - 1)) || ((uintptr_t)bias & 3))
     return GEMM_ERR_MISALIGNED;
-  int rc = check_device();
+  int rc = check_device_gfx950();
   if (rc != GEMM_OK) return rc;
   hipError_t e = plan->cfg->launch[d.dtype_a](*plan, A, B, C, bias, (hipStream_t)hip_stream);
   if (e != hipSuccess) return GEMM_ERR_LAUNCH;

@@ -25,8 +25,12 @@ def test_every_declared_symbol_is_exported(g):
     names = set(re.findall(r"\b(gemm_[a-z_]+)\s*\(", header))
     assert {"gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
             "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune"} <= names
+    rope = open(os.path.join(ROOT, "include", "rope.h")).read()
+    rope = re.sub(r"/\*.*?\*/", "", rope, flags=re.S)
+    rope_names = set(re.findall(r"\b(rope_[a-z_]+)\s*\(", rope))
+    assert rope_names == {"rope_apply"}
     lib = ctypes.CDLL(g.library_path())
-    for n in names:
+    for n in names | rope_names:
         assert hasattr(lib, n), n
 
 
@@ -34,6 +38,31 @@ def test_binding_exposes_the_same_names(g):
     for n in ("gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
               "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune"):
         assert callable(getattr(g, n))
+
+
+def test_rope_argument_checks_need_no_device(g):
+    """Everything rope_apply rejects is rejected on the host, before any device call."""
+    def status(desc, tensors, cos=0x1000, sin=0x2000):
+        try:
+            g.rope_apply(desc, tensors, cos, sin, stream=0)
+        except g.GemmError as e:
+            return e.status
+        return 0
+    t = g.RopeTensor(0x10000, 0x20000, heads=4)
+    ok = dict(batch=2, seq=8, head_dim=64)
+    assert status(g.RopeDesc(**ok), [g.RopeTensor(0, 0x20000, heads=4)]) == -1
+    assert status(g.RopeDesc(**ok), [t], cos=0) == -1
+    assert status(g.RopeDesc(batch=2, seq=8, head_dim=63), [t]) == -2          # odd head_dim
+    assert status(g.RopeDesc(batch=0, seq=8, head_dim=64), [t]) == -2
+    assert status(g.RopeDesc(**ok), [t, t, t]) == -2                            # at most two tensors
+    assert status(g.RopeDesc(**ok), [g.RopeTensor(0x10000, 0x20000, heads=0)]) == -2
+    assert status(g.RopeDesc(**ok, dtype=5), [t]) == -8
+    assert status(g.RopeDesc(**ok, dtype=g.BF16, table_dtype=g.F16), [t]) == -4
+    assert status(g.RopeDesc(**ok, table_stride_b=100), [t]) == -3              # tables of batches overlap
+    assert status(g.RopeDesc(**ok), [g.RopeTensor(0x10000, 0x20000, heads=4, x_strides=(0, 64, 0))]) == -3
+    assert status(g.RopeDesc(**ok), [g.RopeTensor(0x10000, 0x20000, heads=4, x_strides=(2048, 32, 256))]) == -3
+    assert status(g.RopeDesc(**ok), [g.RopeTensor(0x10001, 0x20000, heads=4)]) == -5
+    assert status(g.RopeDesc(**ok), [t], cos=0x1002) == -5                      # fp32 table, 2-byte aligned
 
 
 def _status(g, **kw):
