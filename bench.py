@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--splitk", type=int, default=None,
+                    help="plan the product as split-K with this many K slices (0 = built-in choice); "
+                         "the workspace is allocated once, outside the timed region")
     ap.add_argument("--workload", default="square_8192", choices=sorted(wl.WORKLOADS) + sorted(wl.ROPE_WORKLOADS))
     ap.add_argument("--config", default=None, help="tile configuration name (default: built-in choice)")
     ap.add_argument("--tune", action="store_true",
@@ -254,8 +257,10 @@ def main():
         odt0 = wl.TORCH_DTYPE[w.dtype]
         cfg, _ = g.gemm_tune(desc, A.to(dev), B.to(dev), torch.empty((w.batch, w.M, w.N), dtype=odt0, device=dev),
                              None if bias is None else bias.to(dev), min_seconds=0.2)
-    plan = g.gemm_create_config(desc, cfg)
+    plan = g.gemm_create_config(desc, cfg) if args.splitk is None else g.gemm_create_splitk(desc, args.splitk)
     info = plan.info()
+    ws_bytes = g.gemm_workspace_bytes(plan)
+    ws = torch.empty(max(ws_bytes, 16) // 4, dtype=torch.float32, device=dev) if ws_bytes else None
 
     # HBM-bound shapes: rotate through enough distinct copies of the operands that
     # the 256 MB last-level cache cannot hold them (no reuse between launches).
@@ -272,7 +277,10 @@ def main():
 
     def step(i):
         j = i % nbuf
-        g.gemm_run(plan, Ad[j], Bd[j], Cd[j], biasd, stream)
+        if ws is None:
+            g.gemm_run(plan, Ad[j], Bd[j], Cd[j], biasd, stream)
+        else:
+            g.gemm_run_workspace(plan, Ad[j], Bd[j], Cd[j], biasd, ws, ws_bytes, stream)
 
     if args.copy_calibration:
         # a plain copy of known size: reads 1 GiB and writes 1 GiB

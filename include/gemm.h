@@ -68,7 +68,8 @@ enum {
   GEMM_ERR_LAUNCH = -7,       /* the HIP runtime refused the launch */
   GEMM_ERR_BAD_ENUM = -8,     /* an enum field holds a value outside its range */
   GEMM_ERR_BAD_CONFIG = -9,   /* tile configuration index unknown or not applicable */
-  GEMM_ERR_BAD_SCALE = -10    /* a *_SCALE epilogue with a scale that is not finite */
+  GEMM_ERR_BAD_SCALE = -10,   /* a *_SCALE epilogue with a scale that is not finite */
+  GEMM_ERR_WORKSPACE = -11    /* the plan needs a workspace (gemm_run_workspace), or the one given is too small / misaligned */
 };
 
 /*
@@ -144,6 +145,30 @@ int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C,
  */
 int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, const void* bias,
               void* hip_stream, double min_seconds, int* best_config, float* us_per_config);
+
+/*
+ * Split-K: for products with few output tiles and a long K (too few tiles to occupy the 256
+ * CUs), K is cut into `splits` equal slices that are multiplied side by side into fp32
+ * partial results in a caller-provided workspace, and a second kernel adds the slices (in
+ * a fixed order), applies the epilogue and writes C.  This is the "global coordination,
+ * multi-pass with synchronisation" level of the paper's taxonomy (Sec. 3.2, d_sync = 3).
+ *
+ * gemm_create_splitk - as gemm_create, for batch == 1 problems the matrix-core kernels can
+ *   take (16-bit operands, K-contiguous A and B, K a multiple of 8*splits).  splits >= 1, or
+ *   0 for a built-in choice (which may be 1).  GEMM_ERR_UNSUPPORTED if the problem or the
+ *   split cannot be served.
+ * gemm_workspace_bytes - bytes of device memory the plan needs as workspace (0 for plans of
+ *   gemm_create / gemm_create_config): splits * M * N * 4.
+ * gemm_run_workspace - as gemm_run; `workspace` is a DEVICE pointer, 16-byte aligned, of at
+ *   least gemm_workspace_bytes(plan) bytes, owned by the caller, overwritten by the call and
+ *   free to re-use once the work enqueued here has finished.  Two launches on `hip_stream`.
+ *   Also runs plans that need no workspace (workspace may then be NULL).
+ * gemm_run on a split-K plan returns GEMM_ERR_WORKSPACE.
+ */
+int gemm_create_splitk(const gemm_desc_t* desc, int splits, gemm_plan_t** out_plan);
+size_t gemm_workspace_bytes(const gemm_plan_t* plan);
+int gemm_run_workspace(const gemm_plan_t* plan, const void* A, const void* B, void* C,
+                       const void* bias, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* gemm_destroy - release a plan.  NULL is a no-op that returns GEMM_OK. */
 int gemm_destroy(gemm_plan_t* plan);

@@ -118,6 +118,12 @@ def load_library():
     lib.gemm_status_string.argtypes = [ctypes.c_int]
     lib.gemm_plan_info.restype = ctypes.c_int
     lib.gemm_plan_info.argtypes = [ctypes.c_void_p, ctypes.c_char_p, ctypes.c_size_t]
+    lib.gemm_create_splitk.restype = ctypes.c_int
+    lib.gemm_create_splitk.argtypes = [ctypes.POINTER(GemmDesc), ctypes.c_int, pp]
+    lib.gemm_workspace_bytes.restype = ctypes.c_size_t
+    lib.gemm_workspace_bytes.argtypes = [ctypes.c_void_p]
+    lib.gemm_run_workspace.restype = ctypes.c_int
+    lib.gemm_run_workspace.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_size_t, ctypes.c_void_p]
     lib.rope_apply.restype = ctypes.c_int
     lib.rope_apply.argtypes = [ctypes.POINTER(RopeDesc), ctypes.POINTER(RopeTensor), ctypes.c_int,
                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -170,6 +176,18 @@ def gemm_create(desc: GemmDesc) -> Plan:
     return Plan(out.value, desc)
 
 
+def gemm_create_splitk(desc: GemmDesc, splits: int = 0) -> Plan:
+    """A split-K plan (splits = 0: built-in choice); run it with gemm_run_workspace."""
+    lib = load_library()
+    out = ctypes.c_void_p()
+    _check(lib.gemm_create_splitk(ctypes.byref(desc), splits, ctypes.byref(out)))
+    return Plan(out.value, desc)
+
+
+def gemm_workspace_bytes(plan: Plan) -> int:
+    return int(load_library().gemm_workspace_bytes(plan.handle))
+
+
 def _dev_ptr(x) -> Optional[int]:
     """Device address of a torch tensor (or a raw integer address, or None)."""
     if x is None:
@@ -187,6 +205,19 @@ def gemm_run(plan: Plan, A, B, C, bias=None, stream: Optional[int] = None) -> No
         stream = torch.cuda.current_stream().cuda_stream
     _check(load_library().gemm_run(plan.handle, _dev_ptr(A), _dev_ptr(B), _dev_ptr(C),
                                    _dev_ptr(bias), stream or None))
+
+
+def gemm_run_workspace(plan: Plan, A, B, C, bias=None, workspace=None, workspace_bytes: Optional[int] = None,
+                       stream: Optional[int] = None) -> None:
+    """As gemm_run, with a caller-provided device workspace (a torch tensor or a raw address
+    plus workspace_bytes) for plans that need one."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().gemm_run_workspace(plan.handle, _dev_ptr(A), _dev_ptr(B), _dev_ptr(C), _dev_ptr(bias),
+                                             _dev_ptr(workspace), workspace_bytes, stream or None))
 
 
 def gemm_tune(desc: GemmDesc, A, B, C, bias=None, stream: Optional[int] = None,

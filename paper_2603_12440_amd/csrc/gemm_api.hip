@@ -18,6 +18,7 @@
 #include "mfma_kernel.hpp"
 #include "simt_kernel.hpp"
 #include "skinny_kernel.hpp"
+#include "splitk_kernel.hpp"
 #include "device_check.hpp"
 
 using namespace mi355gemm;
@@ -42,6 +43,10 @@ struct gemm_plan {
   // offsets of its B, C and bias.
   gemm_plan* tail;
   int64_t tail_off_b, tail_off_c, tail_off_bias;
+  // Split-K: `d` is the caller's problem, `inner` the batched product of the K slices into
+  // the fp32 workspace (cfg, grid, ... above are then those of the inner plan, for reporting).
+  int splits;
+  gemm_plan* inner;
 };
 
 namespace {
@@ -342,7 +347,9 @@ double mfma_cost(const Config& c, int64_t M, int64_t N, int64_t K, int64_t batch
   const double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 128 ? 0.75 : 0.84);
   const double tiles = (double)((M + c.bm - 1) / c.bm) * (double)((N + c.bn - 1) / c.bn) * (double)batch;
   const double rounds = (double)(int64_t)((tiles + kNumCUs * per_cu - 1) / (kNumCUs * per_cu));
-  return rounds * area * per_cu / eff * ((double)K + 600.0);
+  // workgroups that actually share a CU (a lone workgroup runs about per_cu times faster)
+  const double sharing = tiles >= (double)kNumCUs * per_cu ? per_cu : (tiles > kNumCUs ? tiles / kNumCUs : 1.0);
+  return rounds * area * sharing / eff * ((double)K + 600.0);
 }
 
 int best_mfma(const gemm_desc_t& d, double* cost_out) {
@@ -459,12 +466,9 @@ const char* gemm_config_name(int config) {
   return (config >= 0 && config < kNumConfigs) ? kConfigs[config].name : nullptr;
 }
 
-int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_plan) {
-  if (out_plan) *out_plan = nullptr;
-  if (!desc || !out_plan) return GEMM_ERR_NULL;
-  gemm_desc_t d;
-  int rc = resolve(desc, &d);
-  if (rc != GEMM_OK) return rc;
+// Plan for an already resolved descriptor.  allow_two_launches: the built-in choice may
+// plan a second launch against wave quantisation.
+static int create_resolved(const gemm_desc_t& d, int config, bool allow_two_launches, gemm_plan_t** out_plan) {
   if (config < -1 || config >= kNumConfigs) return GEMM_ERR_BAD_CONFIG;
   const bool auto_choice = config == -1;
   if (config == -1) config = choose(d);
@@ -477,7 +481,9 @@ int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_pl
   pl->cfg_index = config;
   pl->tail = nullptr;
   pl->tail_off_b = pl->tail_off_c = pl->tail_off_bias = 0;
-  if (auto_choice && kConfigs[config].kind == KIND_MFMA) {
+  pl->splits = 0;
+  pl->inner = nullptr;
+  if (auto_choice && allow_two_launches && kConfigs[config].kind == KIND_MFMA) {
     double single_cost = 0;
     best_mfma(d, &single_cost);
     int big = -1;                                   // the first 256x256 shape of the table
@@ -494,7 +500,7 @@ int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_pl
       gemm_desc_t rest = d;
       rest.N = d.N - n_first;
       gemm_plan_t* tail = nullptr;
-      if (gemm_create_config(&rest, best_mfma(rest, nullptr), &tail) == GEMM_OK) {
+      if (create_resolved(rest, best_mfma(rest, nullptr), false, &tail) == GEMM_OK) {
         pl->tail = tail;
         pl->tail_off_b = n_first * d.ldb;
         pl->tail_off_c = n_first;
@@ -503,10 +509,121 @@ int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_pl
       }
     }
   }
-  rc = fill_launch_shape(*pl);
+  const int rc = fill_launch_shape(*pl);
   if (rc != GEMM_OK) { gemm_destroy(pl); return rc; }
   *out_plan = pl;
   return GEMM_OK;
+}
+
+int gemm_create_config(const gemm_desc_t* desc, int config, gemm_plan_t** out_plan) {
+  if (out_plan) *out_plan = nullptr;
+  if (!desc || !out_plan) return GEMM_ERR_NULL;
+  gemm_desc_t d;
+  const int rc = resolve(desc, &d);
+  if (rc != GEMM_OK) return rc;
+  return create_resolved(d, config, true, out_plan);
+}
+
+// Slices of K for a split-K plan: the count (up to 64, K a multiple of 8 x slices, whole
+// slabs per slice preferred) that minimises the tile cost model of the sliced product plus
+// the traffic of the fp32 partials (written once, read once; measured at about 2 TB/s, the
+// partials leave the accumulators in 16-byte pieces; in the model's units one microsecond
+// is 2.7e6).
+static int choose_splits(const gemm_desc_t& d) {
+  int best = 1;
+  double best_cost = 0;
+  for (int pass = 0; pass < 2 && best_cost == 0; ++pass) {
+    const int64_t unit = pass == 0 ? 64 : 8;
+    for (int64_t s = 1; s <= 64; ++s) {
+      if (d.K % (s * unit) != 0) continue;
+      gemm_desc_t in = d;
+      in.K = d.K / s;
+      in.batch = (int32_t)s;
+      in.stride_a = in.stride_b = in.K;
+      double cost = 0;
+      if (best_mfma(in, &cost) < 0) continue;
+      cost += 2.0 * (double)s * (double)d.M * (double)d.N * 4.0 * (2.7e6 / 2.0e6);
+      if (best_cost == 0 || cost < best_cost) { best = (int)s; best_cost = cost; }
+    }
+  }
+  return best;
+}
+
+int gemm_create_splitk(const gemm_desc_t* desc, int splits, gemm_plan_t** out_plan) {
+  if (out_plan) *out_plan = nullptr;
+  if (!desc || !out_plan) return GEMM_ERR_NULL;
+  gemm_desc_t d;
+  int rc = resolve(desc, &d);
+  if (rc != GEMM_OK) return rc;
+  if (splits < 0 || splits > 1024) return GEMM_ERR_BAD_DIM;
+  if (d.batch != 1 || d.dtype_a == GEMM_F32) return GEMM_ERR_UNSUPPORTED;
+  if (d.layout_a != GEMM_ROW_MAJOR || d.layout_b != GEMM_COL_MAJOR) return GEMM_ERR_UNSUPPORTED;
+  if (splits == 0) splits = choose_splits(d);
+  if (d.K % ((int64_t)splits * 8) != 0) return GEMM_ERR_UNSUPPORTED;
+  if ((double)splits * (double)d.M * (double)d.N * 4.0 >= 9.0e18) return GEMM_ERR_BAD_DIM;
+  // the K slices as the batches of a product into packed fp32 partials, no epilogue
+  gemm_desc_t in = d;
+  in.K = d.K / splits;
+  in.batch = splits;
+  in.stride_a = in.K;                 // slice s of A starts K/splits columns further on
+  in.stride_b = in.K;
+  in.dtype_c = GEMM_F32;
+  in.layout_c = GEMM_ROW_MAJOR;
+  in.ldc = d.N;
+  in.stride_c = d.M * d.N;
+  in.epilogue = GEMM_EPI_NONE;
+  in.stride_bias = 0;
+  in.scale = 1.0f;
+  const int inner_cfg = best_mfma(in, nullptr);
+  if (inner_cfg < 0) return GEMM_ERR_UNSUPPORTED;
+  gemm_plan_t* inner = nullptr;
+  rc = create_resolved(in, inner_cfg, false, &inner);
+  if (rc != GEMM_OK) return rc;
+  gemm_plan* pl = new (std::nothrow) gemm_plan(*inner);
+  if (!pl) { gemm_destroy(inner); return GEMM_ERR_NULL; }
+  pl->d = d;
+  pl->splits = splits;
+  pl->inner = inner;
+  *out_plan = pl;
+  return GEMM_OK;
+}
+
+size_t gemm_workspace_bytes(const gemm_plan_t* plan) {
+  if (!plan || !plan->inner) return 0;
+  return (size_t)plan->splits * (size_t)plan->d.M * (size_t)plan->d.N * 4;
+}
+
+int gemm_run_workspace(const gemm_plan_t* plan, const void* A, const void* B, void* C,
+                       const void* bias, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!plan) return GEMM_ERR_NULL;
+  if (!plan->inner) return gemm_run(plan, A, B, C, bias, hip_stream);
+  if (!A || !B || !C) return GEMM_ERR_NULL;
+  const gemm_desc_t& d = plan->d;
+  if (epilogue_has_bias(d.epilogue) != (bias != nullptr)) return GEMM_ERR_NULL;
+  if (!workspace || workspace_bytes < gemm_workspace_bytes(plan) || ((uintptr_t)workspace & 15))
+    return GEMM_ERR_WORKSPACE;
+  if (((uintptr_t)C & ((uintptr_t)esize(d.dtype_c) - 1)) || ((uintptr_t)bias & 3)) return GEMM_ERR_MISALIGNED;
+  int rc = gemm_run(plan->inner, A, B, workspace, nullptr, hip_stream);
+  if (rc != GEMM_OK) return rc;
+  SplitKReduceArgs r;
+  r.ws = (const float*)workspace; r.C = C; r.bias = (const float*)bias;
+  r.M = d.M; r.N = d.N;
+  r.c_si = d.layout_c == GEMM_ROW_MAJOR ? d.ldc : 1;
+  r.c_sj = d.layout_c == GEMM_ROW_MAJOR ? 1 : d.ldc;
+  r.splits = plan->splits;
+  r.has_bias = epilogue_has_bias(d.epilogue);
+  r.act = epilogue_activation(d.epilogue);
+  r.scale = d.scale;
+  const int64_t quads = d.M * ((d.N + 3) / 4);
+  const int64_t blocks = (quads + 255) / 256;
+  if (blocks >= ((int64_t)1 << 31)) return GEMM_ERR_BAD_DIM;
+  hipStream_t s = (hipStream_t)hip_stream;
+  switch (d.dtype_c) {
+    case GEMM_F32: splitk_reduce_kernel<float><<<(unsigned)blocks, 256, 0, s>>>(r); break;
+    case GEMM_BF16: splitk_reduce_kernel<bf16_t><<<(unsigned)blocks, 256, 0, s>>>(r); break;
+    default: splitk_reduce_kernel<f16_t><<<(unsigned)blocks, 256, 0, s>>>(r); break;
+  }
+  return hipGetLastError() == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }
 
 int gemm_create(const gemm_desc_t* desc, gemm_plan_t** out_plan) {
@@ -516,6 +633,7 @@ int gemm_create(const gemm_desc_t* desc, gemm_plan_t** out_plan) {
 int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, const void* bias,
              void* hip_stream) {
   if (!plan || !A || !B || !C) return GEMM_ERR_NULL;
+  if (plan->inner) return GEMM_ERR_WORKSPACE;
   const gemm_desc_t& d = plan->d;
   if (epilogue_has_bias(d.epilogue) != (bias != nullptr)) return GEMM_ERR_NULL;
   // The tiled 16-bit kernels move 16-byte pieces; the general kernel only needs
@@ -605,7 +723,13 @@ int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, co
 }
 
 int gemm_destroy(gemm_plan_t* plan) {
-  if (plan) delete plan->tail;
+  if (plan) {
+    if (plan->inner) {                 // a split-K plan is a copy of its inner plan's launch data
+      gemm_destroy(plan->inner);
+    } else {
+      delete plan->tail;
+    }
+  }
   delete plan;
   return GEMM_OK;
 }
@@ -623,6 +747,7 @@ const char* gemm_status_string(int status) {
     case GEMM_ERR_BAD_ENUM: return "enum value out of range";
     case GEMM_ERR_BAD_CONFIG: return "tile configuration unknown or not applicable";
     case GEMM_ERR_BAD_SCALE: return "epilogue scale is not finite";
+    case GEMM_ERR_WORKSPACE: return "plan needs a workspace (gemm_run_workspace), or the workspace is too small or misaligned";
     default: return "unknown status";
   }
 }
@@ -630,6 +755,11 @@ const char* gemm_status_string(int status) {
 int gemm_plan_info(const gemm_plan_t* plan, char* buf, size_t n) {
   if (!plan || (!buf && n)) return GEMM_ERR_NULL;
   const Config& c = *plan->cfg;
+  if (plan->inner) {
+    return std::snprintf(buf, n, "kernel=splitk_%d+%s tile=%dx%dx%d grid=%u,%u,%u block=%u lds=%d workspace=%zu",
+                         plan->splits, c.name, c.bm, c.bn, c.bk, plan->grid.x, plan->grid.y, plan->grid.z,
+                         plan->block.x, c.lds_bytes, gemm_workspace_bytes(plan));
+  }
   if (plan->tail) {
     const Config& t = *plan->tail->cfg;
     return std::snprintf(buf, n, "kernel=%s tile=%dx%dx%d grid=%u,%u,%u block=%u lds=%d columns=0..%lld "

@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported(g):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(gemm_[a-z_]+)\s*\(", header))
     assert {"gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
-            "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune"} <= names
+            "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune",
+            "gemm_create_splitk", "gemm_workspace_bytes", "gemm_run_workspace"} <= names
     rope = open(os.path.join(ROOT, "include", "rope.h")).read()
     rope = re.sub(r"/\*.*?\*/", "", rope, flags=re.S)
     rope_names = set(re.findall(r"\b(rope_[a-z_]+)\s*\(", rope))
@@ -36,8 +37,50 @@ def test_every_declared_symbol_is_exported(g):
 
 def test_binding_exposes_the_same_names(g):
     for n in ("gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
-              "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune"):
+              "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune",
+              "gemm_create_splitk", "gemm_workspace_bytes", "gemm_run_workspace", "rope_apply"):
         assert callable(getattr(g, n))
+
+
+def test_splitk_plans(g):
+    """Split-K planning is host work: slices, workspace size, what it refuses."""
+    p = g.gemm_create_splitk(g.GemmDesc(512, 512, 32768))
+    assert "kernel=splitk_16+mfma_128x128" in p.info() and "grid=16,16,1" in p.info()
+    assert g.gemm_workspace_bytes(p) == 16 * 512 * 512 * 4
+    # a split-K plan cannot run without its workspace
+    with pytest.raises(g.GemmError) as e:
+        g.gemm_run(p, 0x1000, 0x2000, 0x3000, stream=0)
+    assert e.value.status == -11
+    with pytest.raises(g.GemmError) as e:
+        g.gemm_run_workspace(p, 0x1000, 0x2000, 0x3000, None, 0x4000, 1024, stream=0)
+    assert e.value.status == -11                       # too small
+    with pytest.raises(g.GemmError) as e:
+        g.gemm_run_workspace(p, 0x1000, 0x2000, 0x3000, None, 0x4004, 1 << 40, stream=0)
+    assert e.value.status == -11                       # not 16-byte aligned
+    g.gemm_destroy(p)
+    p = g.gemm_create_splitk(g.GemmDesc(256, 256, 4096), splits=4)
+    assert "kernel=splitk_4+" in p.info() and g.gemm_workspace_bytes(p) == 4 * 256 * 256 * 4
+    g.gemm_destroy(p)
+    # many tiles already: the built-in choice does not split
+    p = g.gemm_create_splitk(g.GemmDesc(8192, 8192, 8192))
+    assert "kernel=splitk_1+" in p.info()
+    g.gemm_destroy(p)
+    p = g.gemm_create(g.GemmDesc(512, 512, 512))
+    assert g.gemm_workspace_bytes(p) == 0
+    g.gemm_destroy(p)
+    def status(**kw):
+        splits = kw.pop("splits", 0)
+        try:
+            g.gemm_destroy(g.gemm_create_splitk(g.GemmDesc(**kw), splits))
+        except g.GemmError as e:
+            return e.status
+        return 0
+    assert status(M=256, N=256, K=4096, splits=3) == -4          # 4096 is not a multiple of 8*3
+    assert status(M=256, N=256, K=4096, splits=-1) == -2
+    assert status(M=256, N=256, K=4096, batch=2) == -4
+    assert status(M=256, N=256, K=4096, dtype=g.F32, layout_b=g.ROW_MAJOR) == -4
+    assert status(M=256, N=256, K=4096, layout_a=g.COL_MAJOR) == -4
+    assert status(M=0, N=256, K=4096) == -2
 
 
 def test_rope_argument_checks_need_no_device(g):

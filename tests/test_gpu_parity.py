@@ -402,3 +402,85 @@ def test_split_plan_two_launches(g, oracle):
     assert " + kernel=" in info
     ref = run_oracle(oracle, w, A, B, bias, want=("y",))
     assert np.array_equal(wl.to_float64(C), ref["y"])
+
+
+# ---- split-K ------------------------------------------------------------------------------------
+
+def run_splitk(g, w, A, B, bias, splits, out_dtype=None, layout_c="row", pad_c=0, ws_slack=0):
+    dev = torch.device("cuda:0")
+    from helpers import gpu_desc
+    c_major, c_minor = (w.M, w.N) if layout_c == "row" else (w.N, w.M)
+    ldc = c_minor + pad_c
+    odt = wl.TORCH_DTYPE[out_dtype or w.dtype]
+    Cd = torch.full((1, c_major, ldc), -777.0, dtype=odt, device=dev)
+    plan = g.gemm_create_splitk(gpu_desc(g, w, out_dtype, layout_c, ldc=ldc), splits)
+    info = plan.info()
+    n = g.gemm_workspace_bytes(plan)
+    ws = torch.full((n // 4 + ws_slack,), float("nan"), dtype=torch.float32, device=dev)
+    g.gemm_run_workspace(plan, A.to(dev), B.to(dev), Cd, None if bias is None else bias.to(dev), ws, n)
+    torch.cuda.synchronize()
+    g.gemm_destroy(plan)
+    if ws_slack:
+        assert torch.isnan(ws[n // 4:]).all(), "wrote past the stated workspace size"
+    Ch = Cd.cpu()
+    if pad_c:
+        assert torch.all(Ch[:, :, c_minor:] == -777.0)
+    Ch = Ch[:, :, :c_minor]
+    return (Ch.transpose(1, 2) if layout_c == "col" else Ch).contiguous(), info
+
+
+def test_splitk_exact_and_against_oracle(g, oracle):
+    """Integer data: a split product is bit exact whatever the number of slices (also 1, and
+    slices that end inside a slab); random data with every epilogue family against the oracle."""
+    w = wl.Workload("t", 200, 136, 1536, epilogue="bias_relu", seed_a=3, seed_b=4, seed_bias=5)
+    sa, sb = wl.operand_shapes(w)
+    A = wl.small_integers(sa, 3, -1, 1)
+    B = wl.small_integers(sb, 4, -1, 1)
+    bias = wl.small_integers((w.N,), 5, -3, 3, "f32")
+    want = torch.relu(A[0].double() @ B[0].double().T + bias.double())
+    for splits in (1, 2, 3, 8, 24, 0):        # 1536 / 24 = 64: one slab per slice; 1536 / 3 = 512
+        say(f"split-K exact splits={splits}")
+        C, info = run_splitk(g, w, A, B, bias, splits, out_dtype="f32", pad_c=4, ws_slack=64)
+        say("   ", info)
+        assert torch.equal(C[0].double(), want), splits
+    # slices of 40 columns (less than a slab, K tail path in every slice)
+    w2 = wl.Workload("t", 70, 50, 320, seed_a=6, seed_b=7)
+    sa, sb = wl.operand_shapes(w2)
+    A2, B2 = wl.small_integers(sa, 6, -2, 2), wl.small_integers(sb, 7, -2, 2)
+    C, info = run_splitk(g, w2, A2, B2, None, 8, out_dtype="f32")
+    assert torch.equal(C[0].double(), A2[0].double() @ B2[0].double().T)
+    for epilogue, od, lc in [("none", None, "row"), ("bias_gelu_erf", None, "row"), ("bias_swish_scale", "f32", "col"),
+                             ("relu", None, "col")]:
+        w3 = wl.Workload("t", 300, 264, 4096, dist_b=("normal", 1.5 / 64), epilogue=epilogue, scale=1.5,
+                         dist_bias=("uniform", 1.0), seed_a=21, seed_b=22, seed_bias=23)
+        A3, B3, bias3 = wl.make_inputs(w3)
+        ref = run_oracle(oracle, w3, A3, B3, bias3)
+        for splits in (4, 16):
+            say(f"split-K {epilogue} out={od} C {lc}-major splits={splits}")
+            C, info = run_splitk(g, w3, A3, B3, bias3, splits, out_dtype=od, layout_c=lc, pad_c=8)
+            assert_parity(w3, C, ref, A3, B3, bias3, out_dtype=od)
+    # fp16
+    w4 = wl.Workload("t", 128, 128, 2048, dtype="f16", dist_b=("normal", 1.0 / 45), seed_a=31, seed_b=32)
+    A4, B4, _ = wl.make_inputs(w4)
+    C, info = run_splitk(g, w4, A4, B4, None, 8)
+    assert_parity(w4, C, run_oracle(oracle, w4, A4, B4, None), A4, B4, None)
+
+
+def test_splitk_full_size_against_plain_plan_and_oracle_samples(g, oracle):
+    """The split-K benchmark shape at full size: sampled outputs against the oracle, and the
+    whole result against the single-launch plan (both within the E2 bound of the same oracle
+    values, so they may differ by rounding only)."""
+    from helpers import oracle_problem, e2_bound
+    w = wl.WORKLOADS["smallmn_512x512x32768"]
+    A, B, bias = wl.make_inputs(w)
+    C, info = run_splitk(g, w, A, B, None, 0)
+    say("   ", info)
+    assert "splitk_16" in info
+    pb, pi, pj = wl.sample_points(w, 2000, 77)
+    ref = oracle.ref_gemm_points(oracle_problem(oracle, w), wl.storage_numpy(A), wl.storage_numpy(B), None,
+                                 pb, pi, pj, want=("y", "t", "s"))
+    err = np.abs(wl.to_float64(C)[pb, pi, pj] - ref["y"])
+    assert np.all(err <= e2_bound(w, ref)), float((err / e2_bound(w, ref)).max())
+    C1 = run_gpu(g, w, A, B, None)
+    d = (C.double() - C1.double()).abs().max().item()
+    assert d <= 2.0 ** -7 * C1.double().abs().max().item()

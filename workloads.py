@@ -97,6 +97,9 @@ WORKLOADS = {w.name: w for w in [
     Workload("sigres_8192x16384x4096", 8192, 16384, 4096, dist_a=("normal", _k(4096)),
              dist_b=("normal", 1.5 * _k(4096)), epilogue="bias_sigmoid_scale_residual", scale=0.5,
              dist_bias=("uniform", 1.0), seed_a=5021, seed_b=5022, seed_bias=5023),
+    # few output tiles, long K: the split-K case
+    Workload("smallmn_512x512x32768", 512, 512, 32768, dist_a=("normal", 1.0),
+             dist_b=("normal", _k(32768)), seed_a=6001, seed_b=6002),
     Workload("batched_64x512x512x128", 512, 512, 128, dist_a=("normal", _k(128)),
              dist_b=("normal", _k(128)), batch=64, seed_a=5004, seed_b=5005,
              seed_bias=5006, bound="hbm"),
