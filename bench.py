@@ -146,6 +146,16 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
                       f"batch 0, fp64 triple loop, {t:.2f} s wall"}
 
 
+def copy_calibration(dev):
+    """A plain device copy of known size (reads 1 GiB, writes 1 GiB): the yardstick the byte
+    counters of a profiler run are scaled by."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_rope(args, g, dev):
     """A rotary-embedding workload: one step = the query and the key tensor of a layer rotated in
     one launch (include/rope.h).  HBM-bound: algorithmic bytes = every element read and written once."""
@@ -166,6 +176,9 @@ def bench_rope(args, g, dev):
 
     def step(i):
         g.rope_apply(desc, sets[i % nbuf], cosd, sind, stream)
+
+    if args.copy_calibration:
+        copy_calibration(dev)
 
     for i in range(args.warmup):
         step(i)
@@ -283,12 +296,7 @@ def main():
             g.gemm_run_workspace(plan, Ad[j], Bd[j], Cd[j], biasd, ws, ws_bytes, stream)
 
     if args.copy_calibration:
-        # a plain copy of known size: reads 1 GiB and writes 1 GiB
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration(dev)
 
     for i in range(args.warmup):
         step(i)
