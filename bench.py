@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--tune", action="store_true",
                     help="pick the tile configuration with gemm_tune (times every applicable one first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-measured-peak", action="store_true",
+                    help="skip the MFMA-only / streaming-read probe that the roofline fraction is also related to")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling HBM byte counters under a profiler)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -146,6 +148,26 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
                       f"batch 0, fp64 triple loop, {t:.2f} s wall"}
 
 
+def measured_peak(g, dev, bound, dtype):
+    """What the hardware delivers when it does nothing else (include/probe.h): an MFMA-only register
+    loop for the matrix-core bound, a streaming read of 1.25 GiB for the HBM bound.  None for the
+    other bounds."""
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    if bound == "mfma":
+        code = g.F16 if dtype == "f16" else g.BF16
+        return {"value": round(g.probe_mfma_peak(code, sink, min_seconds=0.3), 1), "unit": "TFLOP/s",
+                "what": "v_mfma_f32_32x32x16 register loop, 8 waves per CU, fixed pseudo-random operands",
+                "value_fresh_operands": round(g.probe_mfma_peak(code, sink, min_seconds=0.3, refresh_operands=True), 1)}
+    if bound == "hbm":
+        n = 5 << 28
+        buf = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        out = {"value": round(g.probe_read_peak(buf, n, sink, min_seconds=0.3), 1), "unit": "GB/s",
+               "what": "streaming read of 1.25 GiB, 16 KB per wave, non-temporal"}
+        del buf
+        return out
+    return None
+
+
 def copy_calibration(dev):
     """A plain device copy of known size (reads 1 GiB, writes 1 GiB): the yardstick the byte
     counters of a profiler run are scaled by."""
@@ -207,6 +229,10 @@ def bench_rope(args, g, dev):
         "roofline": {"bound": "hbm", "achieved": round(achieved, 3), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": measured_traffic(w.name)},
     }
+    if not args.no_measured_peak and not args.copy_calibration:
+        mp = measured_peak(g, dev, "hbm", w.dtype)
+        out["roofline"]["measured_peak"] = mp
+        out["roofline"]["frac_of_measured"] = round(achieved / mp["value"], 4)
     ok = True
     if not args.no_cpu_baseline:
         import oracle
@@ -333,6 +359,11 @@ def main():
         "roofline": {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": runit,
                      "frac": round(achieved / peak, 4), "traffic": measured_traffic(w.name)},
     }
+    if not args.no_measured_peak and not args.copy_calibration:
+        mp = measured_peak(g, dev, bound, w.dtype)
+        if mp is not None:
+            out["roofline"]["measured_peak"] = mp
+            out["roofline"]["frac_of_measured"] = round(achieved / mp["value"], 4)
     ok = True
     if not args.no_cpu_baseline:
         # the paper's "no result reuse" rule: the last timed launch's output is checked

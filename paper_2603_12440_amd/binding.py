@@ -124,6 +124,12 @@ def load_library():
     lib.gemm_workspace_bytes.argtypes = [ctypes.c_void_p]
     lib.gemm_run_workspace.restype = ctypes.c_int
     lib.gemm_run_workspace.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_size_t, ctypes.c_void_p]
+    lib.probe_mfma_peak.restype = ctypes.c_int
+    lib.probe_mfma_peak.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double,
+                                    ctypes.POINTER(ctypes.c_double)]
+    lib.probe_read_peak.restype = ctypes.c_int
+    lib.probe_read_peak.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
     lib.rope_apply.restype = ctypes.c_int
     lib.rope_apply.argtypes = [ctypes.POINTER(RopeDesc), ctypes.POINTER(RopeTensor), ctypes.c_int,
                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -271,3 +277,26 @@ def rope_apply(desc: RopeDesc, tensors, cos, sin, stream: Optional[int] = None) 
     arr = (RopeTensor * len(tensors))(*tensors)
     _check(load_library().rope_apply(ctypes.byref(desc), arr, len(tensors), _dev_ptr(cos), _dev_ptr(sin),
                                      stream or None))
+
+
+def probe_mfma_peak(dtype: int, sink, stream: Optional[int] = None, min_seconds: float = 0.3,
+                    refresh_operands: bool = False) -> float:
+    """TFLOP/s of an MFMA-only register loop on the current device (blocks until done)."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    out = ctypes.c_double(0.0)
+    _check(load_library().probe_mfma_peak(dtype, int(refresh_operands), _dev_ptr(sink), stream or None,
+                                          min_seconds, ctypes.byref(out)))
+    return out.value
+
+
+def probe_read_peak(src, nbytes: int, sink, stream: Optional[int] = None, min_seconds: float = 0.3) -> float:
+    """GB/s of a streaming read of `nbytes` (>= 1 GiB) of the device buffer `src` (blocks until done)."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    out = ctypes.c_double(0.0)
+    _check(load_library().probe_read_peak(_dev_ptr(src), nbytes, _dev_ptr(sink), stream or None, min_seconds,
+                                          ctypes.byref(out)))
+    return out.value

@@ -8,7 +8,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmi355gemm.so")
-SOURCES = [os.path.join(CSRC, "gemm_api.hip"), os.path.join(CSRC, "rope_api.hip")]
+SOURCES = [os.path.join(CSRC, "gemm_api.hip"), os.path.join(CSRC, "rope_api.hip"),
+           os.path.join(CSRC, "probe_api.hip")]
 
 
 def _hipcc() -> str:
@@ -25,6 +26,7 @@ def sources_newer_than_lib() -> bool:
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
     deps.append(os.path.join(os.path.dirname(HERE), "include", "gemm.h"))
     deps.append(os.path.join(os.path.dirname(HERE), "include", "rope.h"))
+    deps.append(os.path.join(os.path.dirname(HERE), "include", "probe.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 

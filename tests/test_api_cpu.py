@@ -30,8 +30,12 @@ def test_every_declared_symbol_is_exported(g):
     rope = re.sub(r"/\*.*?\*/", "", rope, flags=re.S)
     rope_names = set(re.findall(r"\b(rope_[a-z_]+)\s*\(", rope))
     assert rope_names == {"rope_apply"}
+    probe = open(os.path.join(ROOT, "include", "probe.h")).read()
+    probe = re.sub(r"/\*.*?\*/", "", probe, flags=re.S)
+    probe_names = set(re.findall(r"\b(probe_[a-z_]+)\s*\(", probe))
+    assert probe_names == {"probe_mfma_peak", "probe_read_peak"}
     lib = ctypes.CDLL(g.library_path())
-    for n in names | rope_names:
+    for n in names | rope_names | probe_names:
         assert hasattr(lib, n), n
 
 
@@ -40,6 +44,19 @@ def test_binding_exposes_the_same_names(g):
               "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune",
               "gemm_create_splitk", "gemm_workspace_bytes", "gemm_run_workspace", "rope_apply"):
         assert callable(getattr(g, n))
+
+
+def test_probe_argument_checks_need_no_device(g):
+    for call, want in [(lambda: g.probe_mfma_peak(g.BF16, 0, stream=0), -1),
+                       (lambda: g.probe_mfma_peak(g.F32, 0x1000, stream=0), -4),
+                       (lambda: g.probe_mfma_peak(g.BF16, 0x1002, stream=0), -5),
+                       (lambda: g.probe_read_peak(0, 1 << 30, 0x1000, stream=0), -1),
+                       (lambda: g.probe_read_peak(0x10000, 1 << 20, 0x1000, stream=0), -2),      # too small
+                       (lambda: g.probe_read_peak(0x10000, (1 << 30) + 16, 0x1000, stream=0), -2),
+                       (lambda: g.probe_read_peak(0x10008, 1 << 30, 0x1000, stream=0), -5)]:
+        with pytest.raises(g.GemmError) as e:
+            call()
+        assert e.value.status == want
 
 
 def test_splitk_plans(g):
