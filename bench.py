@@ -31,6 +31,7 @@ sys.path.insert(0, ROOT)
 import workloads as wl  # noqa: E402
 
 PEAK_MFMA_TFLOPS = 2516.6     # dense bf16/fp16: 256 CU x 4096 FLOP/clk x 2.4 GHz
+PEAK_MFMA_F8_TFLOPS = 5033.2  # dense fp8: twice that
 PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3
 
@@ -82,11 +83,11 @@ def measured_traffic(workload):
 
 
 def gpu_desc(g, w):
-    dt = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16}
+    dt = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16, "f8": g.F8E4M3}
     lay = {"row": g.ROW_MAJOR, "col": g.COL_MAJOR}
-    return g.GemmDesc(w.M, w.N, w.K, dtype=dt[w.dtype], layout_a=lay[w.layout_a],
-                      layout_b=lay[w.layout_b], epilogue=g.EPILOGUES[w.epilogue], batch=w.batch,
-                      scale=w.scale)
+    return g.GemmDesc(w.M, w.N, w.K, dtype=dt[w.dtype], dtype_c=dt[w.out_dtype or w.dtype],
+                      layout_a=lay[w.layout_a], layout_b=lay[w.layout_b],
+                      epilogue=g.EPILOGUES[w.epilogue], batch=w.batch, scale=w.scale)
 
 
 def cpu_baseline(w, A, B, bias, target_s, gpu_out):
@@ -95,7 +96,7 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
     check sampled entries of the GPU result of the last timed launch against it."""
     import oracle
     oracle.build()
-    dt = {"f32": oracle.DTYPE_F32, "bf16": oracle.DTYPE_BF16, "f16": oracle.DTYPE_F16}
+    dt = {"f32": oracle.DTYPE_F32, "bf16": oracle.DTYPE_BF16, "f16": oracle.DTYPE_F16, "f8": oracle.DTYPE_F8E4M3}
     lay = {"row": oracle.ROW_MAJOR, "col": oracle.COL_MAJOR}
     epi = {"none": oracle.EPI_NONE, "bias": oracle.EPI_BIAS, "bias_relu": oracle.EPI_BIAS_RELU,
            "bias_gelu_erf": oracle.EPI_BIAS_GELU_ERF, "bias_gelu_tanh": oracle.EPI_BIAS_GELU_TANH,
@@ -117,7 +118,7 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
     pb, pi, pj = wl.sample_points(w, 2048, 99)
     ref = oracle.ref_gemm_points(oracle_problem(oracle, w), a, b, bz, pb, pi, pj, want=("y", "t", "s"))
     got = gpu_out.to(torch.float64).numpy()[pb, pi, pj]
-    u_out = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24}[w.dtype]
+    u_out = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24}[w.out_dtype or w.dtype]
     acc = 1.13 * w.K * 2.0 ** -24 * ref["s"] + 16 * 2.0 ** -24 * (np.abs(ref["t"]) + 1.0)
     bound = acc + u_out * (np.abs(ref["y"]) + acc) * 1.001 + 1e-30
     matches = bool(np.all(np.abs(got - ref["y"]) <= bound))
@@ -153,7 +154,7 @@ def measured_peak(g, dev, bound, dtype):
     loop for the matrix-core bound, a streaming read of 1.25 GiB for the HBM bound.  None for the
     other bounds."""
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
-    if bound == "mfma":
+    if bound == "mfma" and dtype in ("bf16", "f16"):
         code = g.F16 if dtype == "f16" else g.BF16
         return {"value": round(g.probe_mfma_peak(code, sink, min_seconds=0.3), 1), "unit": "TFLOP/s",
                 "what": "v_mfma_f32_32x32x16 register loop, 8 waves per CU, fixed pseudo-random operands",
@@ -309,7 +310,7 @@ def main():
         nbuf = min(nbuf, 64)
     Ad = [A.to(dev) for _ in range(nbuf)]
     Bd = [B.to(dev) for _ in range(nbuf)]
-    odt = wl.TORCH_DTYPE[w.dtype]
+    odt = wl.TORCH_DTYPE[w.out_dtype or w.dtype]
     Cd = [torch.empty((w.batch, w.M, w.N), dtype=odt, device=dev) for _ in range(nbuf)]
     biasd = bias.to(dev) if bias is not None else None
     stream = torch.cuda.current_stream().cuda_stream
@@ -345,7 +346,7 @@ def main():
     else:
         metric, unit = "GEMM throughput (2MNK / time)", "TFLOP/s"
         value = w.flops / (ms_per_step * 1e-3) / 1e12
-        peak = PEAK_FP32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_TFLOPS
+        peak = {"f32": PEAK_FP32_TFLOPS, "f8": PEAK_MFMA_F8_TFLOPS}.get(w.dtype, PEAK_MFMA_TFLOPS)
         achieved, bound, runit = w.flops / (kern_ms * 1e-3) / 1e12, ("alu" if w.dtype == "f32" else "mfma"), "TFLOP/s"
 
     out = {

@@ -29,7 +29,10 @@ extern "C" {
 
 typedef struct gemm_plan gemm_plan_t;          /* opaque, owned by the library */
 
-typedef enum { GEMM_F32 = 0, GEMM_BF16 = 1, GEMM_F16 = 2 } gemm_dtype_t;
+/* GEMM_F8E4M3: 8-bit floating point, OCP E4M3 (bias 7, no infinities, S.1111.111 = NaN, max 448);
+ * operands only (the "reduced precision" direction of the paper's case study, Sec. 4): C is then
+ * GEMM_BF16 or GEMM_F32.  Products of two such values are exact in fp32; accumulation is fp32. */
+typedef enum { GEMM_F32 = 0, GEMM_BF16 = 1, GEMM_F16 = 2, GEMM_F8E4M3 = 3 } gemm_dtype_t;
 typedef enum { GEMM_ROW_MAJOR = 0, GEMM_COL_MAJOR = 1 } gemm_layout_t;
 
 /* Epilogues.  bias is a length-N fp32 vector added to every row (one value per
@@ -89,7 +92,8 @@ typedef struct {
   int64_t M, N, K;
   int32_t layout_a, layout_b, layout_c;          /* gemm_layout_t */
   int64_t lda, ldb, ldc;
-  int32_t dtype_a, dtype_b, dtype_c, dtype_bias; /* gemm_dtype_t; dtype_a == dtype_b; dtype_c is dtype_a or F32; bias F32 */
+  int32_t dtype_a, dtype_b, dtype_c, dtype_bias; /* gemm_dtype_t; dtype_a == dtype_b; dtype_c is dtype_a or F32
+                                                    (BF16 or F32 for F8E4M3 operands); bias F32 */
   int32_t epilogue;                              /* gemm_epilogue_t */
   int32_t batch;                                 /* >= 1 */
   int64_t stride_a, stride_b, stride_c, stride_bias;
@@ -154,7 +158,7 @@ int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, co
  * multi-pass with synchronisation" level of the paper's taxonomy (Sec. 3.2, d_sync = 3).
  *
  * gemm_create_splitk - as gemm_create, for batch == 1 problems the matrix-core kernels can
- *   take (16-bit operands, K-contiguous A and B, K a multiple of 8*splits).  splits >= 1, or
+ *   take (16-bit or fp8 operands, K-contiguous A and B, every slice a whole number of 16-byte pieces).  splits >= 1, or
  *   0 for a built-in choice (which may be 1).  GEMM_ERR_UNSUPPORTED if the problem or the
  *   split cannot be served.
  * gemm_workspace_bytes - bytes of device memory the plan needs as workspace (0 for plans of

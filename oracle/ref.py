@@ -1,7 +1,7 @@
 """ctypes front end of the C oracle (ref_gemm.c).  TEST INFRASTRUCTURE ONLY.
 
 Operands are passed as flat numpy storage buffers: float32 for fp32, uint16 bit
-patterns for bf16 / fp16.  Results come back as float64 arrays.
+patterns for bf16 / fp16, uint8 bit patterns for 8-bit E4M3.  Results come back as float64 arrays.
 """
 from __future__ import annotations
 
@@ -17,7 +17,7 @@ _SRC = os.path.join(_HERE, "ref_gemm.c")
 _SRC_ROPE = os.path.join(_HERE, "ref_rope.c")
 _LIB = os.path.join(_HERE, "libref_gemm.so")
 
-DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
+DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3 = 0, 1, 2, 3
 ROW_MAJOR, COL_MAJOR = 0, 1
 (EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
  EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
@@ -116,6 +116,8 @@ def _load():
         lib.ref_bf16_bits_to_double.argtypes = [ctypes.c_uint16]
         lib.ref_f16_bits_to_double.restype = ctypes.c_double
         lib.ref_f16_bits_to_double.argtypes = [ctypes.c_uint16]
+        lib.ref_f8e4m3_bits_to_double.restype = ctypes.c_double
+        lib.ref_f8e4m3_bits_to_double.argtypes = [ctypes.c_uint8]
         lib.ref_f32_to_bf16_rne.restype = ctypes.c_uint16
         lib.ref_f32_to_bf16_rne.argtypes = [ctypes.c_float]
         lib.ref_f32_to_f16_rne.restype = ctypes.c_uint16
@@ -135,7 +137,7 @@ def _load():
 
 
 def _np_dtype(code: int):
-    return np.float32 if code == DTYPE_F32 else np.uint16
+    return np.float32 if code == DTYPE_F32 else (np.uint8 if code == DTYPE_F8E4M3 else np.uint16)
 
 
 def _operand(x, code: int, need: int, name: str) -> np.ndarray:
@@ -247,6 +249,10 @@ def sigmoid(t: float) -> float:
 
 def num_threads() -> int:
     return _load().ref_num_threads()
+
+
+def f8e4m3_bits_to_double(bits: int) -> float:
+    return _load().ref_f8e4m3_bits_to_double(bits)
 
 
 def bf16_bits_to_double(bits: int) -> float:

@@ -41,6 +41,23 @@ double ref_f16_bits_to_double(uint16_t bits) {
   return sign ? -v : v;
 }
 
+/* OCP 8-bit floating point E4M3: 1 sign bit, 4 exponent bits (bias 7), 3 significand bits.
+ * No infinities; S.1111.111 is NaN; exponent field 15 otherwise encodes ordinary numbers
+ * (largest: 1.75 * 2^8 = 448); exponent field 0 holds zero and the subnormals f/8 * 2^-6. */
+double ref_f8e4m3_bits_to_double(uint8_t bits) {
+  int sign = (bits >> 7) & 1;
+  int e = (bits >> 3) & 0xf;
+  int f = bits & 0x7;
+  double v;
+  if (e == 0)
+    v = ldexp((double)f, -9);
+  else if (e == 15 && f == 7)
+    v = NAN;
+  else
+    v = ldexp(1.0 + (double)f / 8.0, e - 7);
+  return sign ? -v : v;
+}
+
 /* fp32 -> bf16, round to nearest, ties to even, on the bit pattern. */
 uint16_t ref_f32_to_bf16_rne(float x) {
   uint32_t u;
@@ -75,6 +92,7 @@ static inline double load_elem(const void* base, int dtype, int64_t idx) {
   switch (dtype) {
     case REF_F32:  return (double)((const float*)base)[idx];
     case REF_BF16: return ref_bf16_bits_to_double(((const uint16_t*)base)[idx]);
+    case REF_F8E4M3: return ref_f8e4m3_bits_to_double(((const uint8_t*)base)[idx]);
     default:       return ref_f16_bits_to_double(((const uint16_t*)base)[idx]);
   }
 }

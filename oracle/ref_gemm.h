@@ -21,7 +21,7 @@
  *   swish_scale(t)            = c * t * sigma(t)
  *   sigmoid_scale_residual(t) = c * sigma(t) + t     (the residual is the GEMM output itself)
  *
- * Every stored operand element (fp32, bf16 or fp16) is converted exactly to
+ * Every stored operand element (fp32, bf16, fp16 or 8-bit E4M3) is converted exactly to
  * fp64 first; products of two such values are exact in fp64.  Outputs stay in
  * fp64, never rounded to a storage type.
  *
@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-enum { REF_F32 = 0, REF_BF16 = 1, REF_F16 = 2 };
+enum { REF_F32 = 0, REF_BF16 = 1, REF_F16 = 2, REF_F8E4M3 = 3 };   /* F8E4M3: OCP 8-bit float, operands only */
 enum { REF_ROW_MAJOR = 0, REF_COL_MAJOR = 1 };
 enum {
   REF_EPI_NONE = 0,
@@ -58,7 +58,7 @@ typedef struct {
   int64_t M, N, K;
   int32_t layout_a, layout_b;      /* REF_ROW_MAJOR / REF_COL_MAJOR */
   int64_t lda, ldb;                /* leading dimensions in elements (never 0 here) */
-  int32_t dtype_a, dtype_b;        /* REF_F32 / REF_BF16 / REF_F16 */
+  int32_t dtype_a, dtype_b;        /* REF_F32 / REF_BF16 / REF_F16 / REF_F8E4M3 */
   int32_t epilogue;                /* REF_EPI_* */
   int32_t batch;                   /* >= 1 */
   int64_t stride_a, stride_b;      /* elements between consecutive batches */
@@ -81,6 +81,7 @@ int ref_gemm_points(const ref_problem_t* p, const void* A, const void* B,
 /* Scalar helpers (exposed so the tests can pin them one by one). */
 double   ref_bf16_bits_to_double(uint16_t bits);
 double   ref_f16_bits_to_double(uint16_t bits);
+double   ref_f8e4m3_bits_to_double(uint8_t bits);
 uint16_t ref_f32_to_bf16_rne(float x);   /* round to nearest, ties to even */
 uint16_t ref_f32_to_f16_rne(float x);
 double   ref_activation(int epilogue, double t);                 /* the epilogues without a scale */

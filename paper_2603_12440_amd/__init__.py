@@ -2,7 +2,7 @@
 Python binding of the C ABI in include/gemm.h and include/rope.h.  All arithmetic happens in the HIP kernels of libmi355gemm.so;
 this package only marshals arguments."""
 from .binding import (  # noqa: F401
-    F32, BF16, F16, ROW_MAJOR, COL_MAJOR,
+    F32, BF16, F16, F8E4M3, ROW_MAJOR, COL_MAJOR,
     EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
     EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
     EPI_SWISH_SCALE, EPI_SIGMOID_SCALE_RESIDUAL, EPILOGUES,

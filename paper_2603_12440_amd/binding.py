@@ -12,7 +12,7 @@ from typing import List, Optional
 HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "libmi355gemm.so")
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, F8E4M3 = 0, 1, 2, 3
 ROW_MAJOR, COL_MAJOR = 0, 1
 (EPI_NONE, EPI_BIAS, EPI_BIAS_RELU, EPI_BIAS_GELU_ERF, EPI_BIAS_GELU_TANH,
  EPI_RELU, EPI_GELU_ERF, EPI_BIAS_SWISH_SCALE, EPI_BIAS_SIGMOID_SCALE_RESIDUAL,
@@ -54,7 +54,7 @@ class GemmDesc(ctypes.Structure):
                  dtype_b=None, dtype_bias=F32, scale=1.0):
         super().__init__(M, N, K, layout_a, layout_b, layout_c, lda, ldb, ldc,
                          dtype, dtype if dtype_b is None else dtype_b,
-                         dtype if dtype_c is None else dtype_c, dtype_bias,
+                         (BF16 if dtype == F8E4M3 else dtype) if dtype_c is None else dtype_c, dtype_bias,
                          epilogue, batch, stride_a, stride_b, stride_c, stride_bias, scale)
 
 

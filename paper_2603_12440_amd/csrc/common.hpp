@@ -11,6 +11,10 @@ namespace mi355gemm {
 
 typedef __bf16 bf16_t;
 typedef _Float16 f16_t;
+// 8-bit floating point, OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 significand bits;
+// no infinities, S.1111.111 is NaN, largest finite value 448): storage only, the matrix
+// cores multiply it directly.
+struct f8e4m3_t { unsigned char bits; };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));

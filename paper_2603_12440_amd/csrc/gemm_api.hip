@@ -60,10 +60,10 @@ struct Config {
   int bm, bn, bk;         // tile (skinny: bm = padded M, bn = workgroups per CU, bk = K per pass)
   int threads;
   int lds_bytes;
-  launch_fn launch[3];    // per storage dtype (GEMM_F32 / BF16 / F16); NULL = not compiled
+  launch_fn launch[4];    // per operand dtype (GEMM_F32 / BF16 / F16 / F8E4M3); NULL = not compiled
 };
 
-inline int esize(int dt) { return dt == GEMM_F32 ? 4 : 2; }
+inline int esize(int dt) { return dt == GEMM_F32 ? 4 : (dt == GEMM_F8E4M3 ? 1 : 2); }
 
 // ---- launchers ---------------------------------------------------------------------
 
@@ -97,7 +97,7 @@ hipError_t launch_simt(const gemm_plan& pl, const void* A, const void* B, void* 
   return launch_simt_typed<TIn, TIn, TM, TN, TK>(pl, A, B, C, bias, s);
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int NS>
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int NS>
 hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
                        const void* bias, hipStream_t s) {
   const gemm_desc_t& d = pl.d;
@@ -115,7 +115,7 @@ hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* 
   a.tiles_n = (int)((d.N + BN - 1) / BN);
   a.group_m = pl.group_m;
   a.xcd_remap = pl.xcd_remap;
-  mfma_gemm_kernel<T, BM, BN, BK, WM, WN, NS><<<pl.grid, pl.block, 0, s>>>(a);
+  mfma_gemm_kernel<T, TO, BM, BN, BK, WM, WN, NS><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
 
@@ -202,8 +202,13 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
 #define MFMA_CFG(BM, BN, BK, WM, WN, NS)                                                   \
   { "mfma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, KIND_MFMA, BM, BN, BK,          \
     64 * WM * WN, MfmaTile<bf16_t, BM, BN, BK, WM, WN, NS>::LDS_BYTES,                     \
-    { nullptr, launch_mfma<bf16_t, BM, BN, BK, WM, WN, NS>,                                \
-      launch_mfma<f16_t, BM, BN, BK, WM, WN, NS> } }
+    { nullptr, launch_mfma<bf16_t, bf16_t, BM, BN, BK, WM, WN, NS>,                        \
+      launch_mfma<f16_t, f16_t, BM, BN, BK, WM, WN, NS> } }
+// fp8 (E4M3) operands, bf16 or fp32 output: the same slabs in bytes (BK is twice as many values)
+#define MFMA8_CFG(BM, BN, BK, WM, WN, NS)                                                  \
+  { "mfma8_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, KIND_MFMA, BM, BN, BK,         \
+    64 * WM * WN, MfmaTile<f8e4m3_t, BM, BN, BK, WM, WN, NS>::LDS_BYTES,                   \
+    { nullptr, nullptr, nullptr, launch_mfma<f8e4m3_t, bf16_t, BM, BN, BK, WM, WN, NS> } }
 
 // bn = workgroups per CU the grid is sized for
 #define SKINNY_CFG(MB, WAVES, PER_CU)                                                      \
@@ -235,6 +240,8 @@ const Config kConfigs[] = {
     MFMA_CFG(256, 128, 64, 2, 2, 2),
     MFMA_CFG(128, 128, 64, 2, 2, 2),
     MFMA_CFG(256, 256, 64, 4, 4, 2),
+    MFMA8_CFG(256, 256, 128, 2, 4, 2),
+    MFMA8_CFG(128, 128, 128, 2, 2, 2),
     SKINNY_CFG(1, 4, 1),
     SKINNY_CFG(2, 4, 1),
     SKINNY_CFG(4, 4, 1),
@@ -261,7 +268,7 @@ bool in_range(int v, int lo, int hi) { return v >= lo && v <= hi; }
 int resolve(const gemm_desc_t* in, gemm_desc_t* out) {
   gemm_desc_t d = *in;
   if (!in_range(d.layout_a, 0, 1) || !in_range(d.layout_b, 0, 1) || !in_range(d.layout_c, 0, 1) ||
-      !in_range(d.dtype_a, 0, 2) || !in_range(d.dtype_b, 0, 2) || !in_range(d.dtype_c, 0, 2) ||
+      !in_range(d.dtype_a, 0, 3) || !in_range(d.dtype_b, 0, 3) || !in_range(d.dtype_c, 0, 3) ||
       !in_range(d.dtype_bias, 0, 2) || !in_range(d.epilogue, 0, GEMM_EPI_SIGMOID_SCALE_RESIDUAL))
     return GEMM_ERR_BAD_ENUM;
   if (epilogue_has_scale(d.epilogue)) {
@@ -302,7 +309,11 @@ int resolve(const gemm_desc_t* in, gemm_desc_t* out) {
     if (d.stride_bias != 0 && d.stride_bias < d.N) return GEMM_ERR_BAD_LD;
   }
   if (d.dtype_a != d.dtype_b) return GEMM_ERR_UNSUPPORTED;
-  if (d.dtype_c != d.dtype_a && d.dtype_c != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
+  if (d.dtype_a == GEMM_F8E4M3) {
+    if (d.dtype_c != GEMM_BF16 && d.dtype_c != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
+  } else if (d.dtype_c != d.dtype_a && d.dtype_c != GEMM_F32) {
+    return GEMM_ERR_UNSUPPORTED;
+  }
   if (d.dtype_bias != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
   *out = d;
   return GEMM_OK;
@@ -316,7 +327,8 @@ bool applicable(const Config& c, const gemm_desc_t& d) {
   // 16-byte pieces: every row start must be 16-byte aligned.
   if (d.layout_a != GEMM_ROW_MAJOR || d.layout_b != GEMM_COL_MAJOR || d.layout_c != GEMM_ROW_MAJOR)
     return false;
-  if (d.K % 8 || d.lda % 8 || d.ldb % 8 || d.stride_a % 8 || d.stride_b % 8) return false;
+  const int64_t epc = 16 / esize(d.dtype_a);                 // operand elements per 16-byte piece
+  if (d.K % epc || d.lda % epc || d.ldb % epc || d.stride_a % epc || d.stride_b % epc) return false;
   if (d.M >= ((int64_t)1 << 31) - 512 || d.N >= ((int64_t)1 << 31) - 512 ||
       d.K >= ((int64_t)1 << 31) - 512)
     return false;
@@ -325,7 +337,8 @@ bool applicable(const Config& c, const gemm_desc_t& d) {
     return d.M <= c.bm && 32 * d.ldb * 2 < ((int64_t)1 << 32) && 32 * d.lda * 2 < ((int64_t)1 << 32) &&
            (d.N + 31) / 32 < ((int64_t)1 << 31);
   // MFMA: per-lane byte offsets inside a tile's row panel are 32-bit.
-  if ((int64_t)c.bm * d.lda * 2 >= ((int64_t)1 << 32) || (int64_t)c.bn * d.ldb * 2 >= ((int64_t)1 << 32))
+  if ((int64_t)c.bm * d.lda * esize(d.dtype_a) >= ((int64_t)1 << 32) ||
+      (int64_t)c.bn * d.ldb * esize(d.dtype_a) >= ((int64_t)1 << 32))
     return false;
   const int64_t tiles = ((d.M + c.bm - 1) / c.bm) * ((d.N + c.bn - 1) / c.bn);
   return tiles < ((int64_t)1 << 31);
@@ -473,7 +486,7 @@ static int create_resolved(const gemm_desc_t& d, int config, bool allow_two_laun
   const bool auto_choice = config == -1;
   if (config == -1) config = choose(d);
   if (config < 0) return GEMM_ERR_UNSUPPORTED;
-  if (!applicable(kConfigs[config], d)) return GEMM_ERR_BAD_CONFIG;
+  if (!applicable(kConfigs[config], d)) return auto_choice ? GEMM_ERR_UNSUPPORTED : GEMM_ERR_BAD_CONFIG;
   gemm_plan* pl = new (std::nothrow) gemm_plan;
   if (!pl) return GEMM_ERR_NULL;
   pl->d = d;
@@ -533,7 +546,8 @@ static int choose_splits(const gemm_desc_t& d) {
   int best = 1;
   double best_cost = 0;
   for (int pass = 0; pass < 2 && best_cost == 0; ++pass) {
-    const int64_t unit = pass == 0 ? 64 : 8;
+    const int64_t epc = 16 / esize(d.dtype_a);
+    const int64_t unit = pass == 0 ? 8 * epc : epc;          // whole slabs, else whole 16-byte pieces
     for (int64_t s = 1; s <= 64; ++s) {
       if (d.K % (s * unit) != 0) continue;
       gemm_desc_t in = d;
@@ -559,7 +573,7 @@ int gemm_create_splitk(const gemm_desc_t* desc, int splits, gemm_plan_t** out_pl
   if (d.batch != 1 || d.dtype_a == GEMM_F32) return GEMM_ERR_UNSUPPORTED;
   if (d.layout_a != GEMM_ROW_MAJOR || d.layout_b != GEMM_COL_MAJOR) return GEMM_ERR_UNSUPPORTED;
   if (splits == 0) splits = choose_splits(d);
-  if (d.K % ((int64_t)splits * 8) != 0) return GEMM_ERR_UNSUPPORTED;
+  if (d.K % ((int64_t)splits * (16 / esize(d.dtype_a))) != 0) return GEMM_ERR_UNSUPPORTED;
   if ((double)splits * (double)d.M * (double)d.N * 4.0 >= 9.0e18) return GEMM_ERR_BAD_DIM;
   // the K slices as the batches of a product into packed fp32 partials, no epilogue
   gemm_desc_t in = d;

@@ -1,4 +1,5 @@
-// Matrix-core GEMM for gfx950: 16-bit operands (bf16 / fp16), fp32 accumulate.
+// Matrix-core GEMM for gfx950: 16-bit operands (bf16 / fp16) or 8-bit floating point
+// (OCP E4M3), fp32 accumulate.
 //
 //   C = act(A . B + bias),  A row-major (K contiguous), B column-major (K
 //   contiguous: the "weight" matrix stored N x K), C row-major.
@@ -37,24 +38,43 @@ template <typename T> struct Frag;
 // ("+a") and, being volatile, the MFMAs keep their program order relative to each
 // other and to the (volatile) fragment reads, which is what the hand-made
 // software pipeline below relies on.
+// A fragment is kParts 16-byte LDS reads per lane: one for the 16-bit types (8 values of K
+// per lane and MFMA), two for fp8, whose v_mfma_f32_32x32x64_f8f6f4 takes 32 values of K per
+// lane (lane l: row l % 32; which 32 values of the step's 64 a lane holds is free as long
+// as A and B agree, so the two reads are the same pair of adjacent 16-byte chunks that two
+// consecutive 16-bit steps would read).  kKStep = values of K one MFMA consumes.
 template <> struct Frag<bf16_t> {
-  typedef bf16x8_t type;
-  static __device__ __forceinline__ void mfma(const type& x, const type& y, f32x16_t& c) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(x), "v"(y));
+  static constexpr int kParts = 1, kKStep = 16;
+  static __device__ __forceinline__ void mfma(const u32x4_t (&x)[1], const u32x4_t (&y)[1], f32x16_t& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(x[0]), "v"(y[0]));
   }
 };
 template <> struct Frag<f16_t> {
-  typedef f16x8_t type;
-  static __device__ __forceinline__ void mfma(const type& x, const type& y, f32x16_t& c) {
-    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(x), "v"(y));
+  static constexpr int kParts = 1, kKStep = 16;
+  static __device__ __forceinline__ void mfma(const u32x4_t (&x)[1], const u32x4_t (&y)[1], f32x16_t& c) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(x[0]), "v"(y[0]));
+  }
+};
+template <> struct Frag<f8e4m3_t> {
+  static constexpr int kParts = 2, kKStep = 64;
+  static __device__ __forceinline__ void mfma(const u32x4_t (&x)[2], const u32x4_t (&y)[2], f32x16_t& c) {
+    typedef int i32x4_t __attribute__((ext_vector_type(4)));
+    typedef int i32x8_t __attribute__((ext_vector_type(8)));
+    const i32x8_t xv = __builtin_shufflevector(__builtin_bit_cast(i32x4_t, x[0]), __builtin_bit_cast(i32x4_t, x[1]),
+                                               0, 1, 2, 3, 4, 5, 6, 7);
+    const i32x8_t yv = __builtin_shufflevector(__builtin_bit_cast(i32x4_t, y[0]), __builtin_bit_cast(i32x4_t, y[1]),
+                                               0, 1, 2, 3, 4, 5, 6, 7);
+    // both operand formats default to fp8 E4M3, no block scaling
+    asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(c) : "v"(xv), "v"(yv));
   }
 };
 
 // ---- LDS layout ------------------------------------------------------------------
-// A slab is rows x BK 16-bit values, i.e. rows x (BK/8) chunks of 16 bytes.
-// Chunk c of row r is stored at chunk slot  r*(BK/8) + (c ^ swz(r)):  the XOR
-// spreads the 32 rows a fragment read touches over all LDS banks.
-template <int BK> __device__ __forceinline__ int swz(int r);
+// A slab is rows x BK values, i.e. rows of 2*HB bytes = HB/8 chunks of 16 bytes (HB = BK
+// for the 16-bit types, BK/2 for fp8).  Chunk c of row r is stored at chunk slot
+// r*(HB/8) + (c ^ swz<HB>(r)):  the XOR spreads the 32 rows a fragment read touches over
+// all LDS banks.
+template <int HB> __device__ __forceinline__ int swz(int r);
 template <> __device__ __forceinline__ int swz<64>(int r) { return (r & 7) ^ ((r >> 3) & 3); }
 template <> __device__ __forceinline__ int swz<32>(int r) {
   return ((r >> 1) & 3) ^ ((r >> 3) & 1);
@@ -166,14 +186,18 @@ struct MfmaTile {
   static constexpr int kWaves = WM * WN;
   static constexpr int WTM = BM / WM, WTN = BN / WN;     // per-wave block
   static constexpr int MT = WTM / 32, NT = WTN / 32;     // 32x32 MFMA tiles per wave
-  static constexpr int CPR = BK / 8;                     // 16-byte chunks per slab row
+  static constexpr int ES = (int)sizeof(T);              // bytes per operand element
+  static constexpr int EPC = 16 / ES;                    // elements per 16-byte chunk
+  static constexpr int ROWB = BK * ES;                   // bytes per slab row
+  static constexpr int HB = ROWB / 2;                    // key of the swizzle
+  static constexpr int CPR = ROWB / 16;                  // 16-byte chunks per slab row
   static constexpr int RPI = 64 / CPR;                   // slab rows one wave-wide load covers
   static constexpr int A_LOADS = BM / RPI / kWaves;      // direct-to-LDS loads per lane, A slab
   static constexpr int B_LOADS = BN / RPI / kWaves;
-  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-  static constexpr int KK = BK / 16;                     // MFMA k-steps per slab
+  static constexpr int KK = BK / Frag<T>::kKStep;        // MFMA k-steps per slab
   static_assert(BM % (RPI * kWaves) == 0 && BN % (RPI * kWaves) == 0, "slab rows must divide over waves");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave block must be a multiple of 32x32");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -182,11 +206,13 @@ struct MfmaTile {
                                     "many MFMAs as reads (wave blocks of at least 2 x 2 MFMA tiles)");
 };
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+// T: operand type; TO: the 16-bit output type (outputs may also be fp32: MfmaArgs::c_f32).
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   typedef MfmaTile<T, BM, BN, BK, WM, WN, NSTAGE> Cfg;
-  typedef typename Frag<T>::type frag_t;
   constexpr int MT = Cfg::MT, NT = Cfg::NT, CPR = Cfg::CPR, RPI = Cfg::RPI;
+  constexpr int ES = Cfg::ES, EPC = Cfg::EPC, ROWB = Cfg::ROWB, HB = Cfg::HB;
+  constexpr int kParts = Frag<T>::kParts;
 
   __shared__ __attribute__((aligned(1024))) unsigned char smem[Cfg::LDS_BYTES];
 
@@ -212,16 +238,16 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
 #pragma unroll
   for (int q = 0; q < Cfg::A_LOADS; ++q) {
     const int r = (wave * Cfg::A_LOADS + q) * RPI + lane / CPR;
-    const int c = (lane % CPR) ^ swz<BK>(r);
+    const int c = (lane % CPR) ^ swz<HB>(r);
     const int rr = min(r, p.M - 1 - row0);
-    a_off[q] = (uint32_t)(((int64_t)rr * p.lda + c * 8) * 2);
+    a_off[q] = (uint32_t)(((int64_t)rr * p.lda + c * EPC) * ES);
   }
 #pragma unroll
   for (int q = 0; q < Cfg::B_LOADS; ++q) {
     const int r = (wave * Cfg::B_LOADS + q) * RPI + lane / CPR;
-    const int c = (lane % CPR) ^ swz<BK>(r);
+    const int c = (lane % CPR) ^ swz<HB>(r);
     const int rr = min(r, p.N - 1 - col0);
-    b_off[q] = (uint32_t)(((int64_t)rr * p.ldb + c * 8) * 2);
+    b_off[q] = (uint32_t)(((int64_t)rr * p.ldb + c * EPC) * ES);
   }
 
   // One direct-to-LDS load: q < A_LOADS fills the A slab, the rest the B slab.  Issued as
@@ -232,7 +258,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   auto issue_one_load = [&](int q, int kt, int stage) {
     const bool is_a = q < Cfg::A_LOADS;
     const int qq = is_a ? q : q - Cfg::A_LOADS;
-    const char* g = (const char*)(is_a ? Ab : Bb) + (int64_t)kt * (BK * 2);
+    const char* g = (const char*)(is_a ? Ab : Bb) + (int64_t)kt * ROWB;
     const uint32_t dst = lds_base + stage * Cfg::STAGE_BYTES + (is_a ? 0 : Cfg::A_BYTES) +
                          (wave * (is_a ? Cfg::A_LOADS : Cfg::B_LOADS) + qq) * 1024;
     const uint32_t off = is_a ? a_off[qq] : b_off[qq];
@@ -249,24 +275,24 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // through registers.  (K is a multiple of 8: chunks are never split.)
   auto issue_loads_tail = [&](int kt, int stage) {
     const int kvalid = p.K - kt * BK;                      // valid columns in this slab
-    const char* ga = (const char*)Ab + (int64_t)kt * (BK * 2);
-    const char* gb = (const char*)Bb + (int64_t)kt * (BK * 2);
+    const char* ga = (const char*)Ab + (int64_t)kt * ROWB;
+    const char* gb = (const char*)Bb + (int64_t)kt * ROWB;
     unsigned char* sa = smem + stage * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024);
     unsigned char* sb = smem + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024);
 #pragma unroll
     for (int q = 0; q < Cfg::A_LOADS; ++q) {
       const int r = (wave * Cfg::A_LOADS + q) * RPI + lane / CPR;
-      const int c = (lane % CPR) ^ swz<BK>(r);
+      const int c = (lane % CPR) ^ swz<HB>(r);
       u32x4_t v = {0u, 0u, 0u, 0u};
-      if (c * 8 < kvalid) v = *(const u32x4_t*)(ga + a_off[q]);
+      if (c * EPC < kvalid) v = *(const u32x4_t*)(ga + a_off[q]);
       *(u32x4_t*)(sa + q * 1024 + lane * 16) = v;
     }
 #pragma unroll
     for (int q = 0; q < Cfg::B_LOADS; ++q) {
       const int r = (wave * Cfg::B_LOADS + q) * RPI + lane / CPR;
-      const int c = (lane % CPR) ^ swz<BK>(r);
+      const int c = (lane % CPR) ^ swz<HB>(r);
       u32x4_t v = {0u, 0u, 0u, 0u};
-      if (c * 8 < kvalid) v = *(const u32x4_t*)(gb + b_off[q]);
+      if (c * EPC < kvalid) v = *(const u32x4_t*)(gb + b_off[q]);
       *(u32x4_t*)(sb + q * 1024 + lane * 16) = v;
     }
   };
@@ -276,13 +302,17 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   const int fr = lane & 31, fh = lane >> 5;
   const int a_row = wm * Cfg::WTM + fr;
   const int b_row = wn * Cfg::WTN + fr;
-  // byte offset of (row, chunk kk*2+fh) = row*BK*2 + (((kk*2+fh) ^ swz(row)) * 16)
-  uint32_t a_rd[Cfg::KK], b_rd[Cfg::KK];
+  // byte offset of (row, chunk c) = row*ROWB + ((c ^ swz(row)) * 16); part j of k-step kk is
+  // chunk (kk*kParts + j)*2 + fh
+  uint32_t a_rd[Cfg::KK][kParts], b_rd[Cfg::KK][kParts];
 #pragma unroll
-  for (int kk = 0; kk < Cfg::KK; ++kk) {
-    a_rd[kk] = a_row * (BK * 2) + (((kk * 2 + fh) ^ swz<BK>(a_row)) * 16);
-    b_rd[kk] = Cfg::A_BYTES + b_row * (BK * 2) + (((kk * 2 + fh) ^ swz<BK>(b_row)) * 16);
-  }
+  for (int kk = 0; kk < Cfg::KK; ++kk)
+#pragma unroll
+    for (int j = 0; j < kParts; ++j) {
+      const int c = (kk * kParts + j) * 2 + fh;
+      a_rd[kk][j] = a_row * ROWB + ((c ^ swz<HB>(a_row)) * 16);
+      b_rd[kk][j] = Cfg::A_BYTES + b_row * ROWB + ((c ^ swz<HB>(b_row)) * 16);
+    }
 
   f32x16_t acc[MT][NT];
 #pragma unroll
@@ -294,15 +324,18 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
 
   // Fragment registers, double-buffered over the MFMA k-steps of a slab: while the
   // MFMAs of step kk run, the LDS reads of step kk+1 are already in flight.
-  frag_t af[2][MT], bf[2][NT];
+  u32x4_t af[2][MT][kParts], bf[2][NT][kParts];
   typedef StepOrder<MT, NT> Ord;
   const uint32_t smem_base = lds_base;
 
   auto read_one = [&](int i, int stage, int kk, int buf) {       // i-th read of the fixed read order
     const uint32_t s = smem_base + stage * Cfg::STAGE_BYTES;
     const int idx = Ord::t.r_idx[i];
-    if (Ord::t.r_isb[i]) lds_read_b128(bf[buf][idx], s + b_rd[kk], idx * (32 * BK * 2));
-    else lds_read_b128(af[buf][idx], s + a_rd[kk], idx * (32 * BK * 2));
+#pragma unroll
+    for (int j = 0; j < kParts; ++j) {
+      if (Ord::t.r_isb[i]) lds_read_b128(bf[buf][idx][j], s + b_rd[kk][j], idx * (32 * ROWB));
+      else lds_read_b128(af[buf][idx][j], s + a_rd[kk][j], idx * (32 * ROWB));
+    }
   };
   auto read_frags = [&](int stage, int kk, int buf) {
 #pragma unroll
@@ -330,7 +363,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       // and min(i, kReads) requests of this step have been issued.
       {
         const int after = (Ord::kReads - 1 - Ord::t.need[i]) + (reads ? (i < Ord::kReads ? i : Ord::kReads) : 0);
-        wait_lgkmcnt_dyn(after);
+        wait_lgkmcnt_dyn(after * kParts);        // (the counter holds 15 at most: larger values wait for 15)
       }
       Frag<T>::mfma(bf[cur][n], af[cur][m], acc[m][n]);
       if (reads && i < Ord::kReads) read_one(i, rs, rk, cur ^ 1);
@@ -394,16 +427,31 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    const int ksteps = (p.K - T_full * BK + 15) / 16;
+    const int ksteps = (p.K - T_full * BK + Frag<T>::kKStep - 1) / Frag<T>::kKStep;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       if (kk < ksteps) {
-        read_frags(0, kk, 0);
-        step(0, false, 0, 0, false, 0, 0);
+        // alternate the fragment buffers as the main loop does: a step's reads must not land
+        // in registers that MFMAs of the step before, still queued, have yet to read
+        read_frags(0, kk, kk & 1);
+        step(kk & 1, false, 0, 0, false, 0, 0);
       }
     }
     wait_lgkmcnt<0>();
   }
+
+  // The MFMAs were issued through inline assembly, so the compiler does not know that the
+  // accumulators are matrix-core results and inserts none of the wait states a vector-ALU
+  // read of a just-written MFMA result needs (there is no hardware interlock: up to 19
+  // cycles after a 16-pass instruction).  Wait once, and route every accumulator through an
+  // (empty) volatile statement placed after the wait, so that no read can be scheduled
+  // above it.  Without this the last k-step of a K tail was lost for the MFMA tiles issued
+  // last whenever nothing else separated it from the epilogue.
+  asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int n = 0; n < NT; ++n) asm volatile("" : "+a"(acc[m][n]));
 
   // ---- epilogue ---------------------------------------------------------------------
   // Lane l of a 32x32 accumulator tile holds row (l % 32) and, in register r,
@@ -433,12 +481,12 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
 
   const bool through_lds = !p.c_f32 && (p.ldc % 8 == 0) && (p.stride_c % 8 == 0) &&
                            (((uintptr_t)p.C & 15) == 0);
-  constexpr int ROWB = Cfg::WTN * 2;           // bytes per row of the wave's block
-  constexpr int CH = ROWB / 16;                // 16-byte chunks per row
+  constexpr int OROWB = Cfg::WTN * 2;           // bytes per row of the wave's block
+  constexpr int CH = OROWB / 16;                // 16-byte chunks per row
   constexpr int RPI2 = 64 / CH;                // rows one wave-wide 16-byte access covers
   static_assert(Cfg::LDS_BYTES >= BM * BN * 2, "the output block must fit the slab stages");
   static_assert(CH >= 8 && 64 % CH == 0, "row of the wave block: at least 128 bytes");
-  unsigned char* wt = smem + wave * (Cfg::WTM * ROWB);
+  unsigned char* wt = smem + wave * (Cfg::WTM * OROWB);
 
   // Each accumulator is read once: + bias, activation, rounding, and out (to LDS or
   // to memory).  `actf` is a compile-time functor: one copy of the loops per activation.
@@ -460,8 +508,8 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
             // chunk q of row r sits at chunk slot q ^ ((r >> 1) & 7): spreads the 32 rows
             // a write instruction touches over the banks
             const int r = m * 32 + fr, q = n * 4 + g;
-            u32x2_t w = {pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3])};
-            *(u32x2_t*)(wt + r * ROWB + ((q ^ ((r >> 1) & 7)) * 16) + fh * 8) = w;
+            u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
+            *(u32x2_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & 7)) * 16) + fh * 8) = w;
           } else {
             // fp32 output, or C rows that are not 16-byte aligned: store from the
             // accumulator layout
@@ -480,14 +528,14 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
                   if (j + e < p.N) c[e] = v[e];
               }
             } else {
-              T* c = (T*)p.C + o;
+              TO* c = (TO*)p.C + o;
               if (full && vec_ok) {
-                u32x2_t w = {pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3])};
+                u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
                 *(u32x2_t*)c = w;
               } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                  if (j + e < p.N) c[e] = from_float<T>(v[e]);
+                  if (j + e < p.N) c[e] = from_float<TO>(v[e]);
               }
             }
           }
@@ -510,15 +558,15 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   }
   if (!through_lds) return;
 
-  T* Cb = (T*)p.C + batch * p.stride_c;
+  TO* Cb = (TO*)p.C + batch * p.stride_c;
 #pragma unroll
   for (int it = 0; it < Cfg::WTM / RPI2; ++it) {
     const int r = it * RPI2 + lane / CH, q = lane % CH;
-    const u32x4_t val = *(const u32x4_t*)(wt + r * ROWB + ((q ^ ((r >> 1) & 7)) * 16));
+    const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & 7)) * 16));
     const int i = row0 + wm * Cfg::WTM + r;
     const int j = col0 + wn * Cfg::WTN + q * 8;
     if (i < p.M && j < p.N) {
-      T* c = Cb + (int64_t)i * p.ldc + j;
+      TO* c = Cb + (int64_t)i * p.ldc + j;
       if (j + 8 <= p.N) {
         __builtin_nontemporal_store(val, (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
       } else {                                 // ragged right edge: element by element

@@ -17,11 +17,11 @@ import workloads as wl
 
 U32 = 2.0 ** -24
 OUT_ROUNDOFF = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24}
-E1_TOL = {"bf16": 2e-3, "f16": 2e-3, "f32": 1e-6}
+E1_TOL = {"bf16": 2e-3, "f16": 2e-3, "f32": 1e-6, "f8": 2e-3}
 
 
 def oracle_codes(o):
-    return ({"f32": o.DTYPE_F32, "bf16": o.DTYPE_BF16, "f16": o.DTYPE_F16},
+    return ({"f32": o.DTYPE_F32, "bf16": o.DTYPE_BF16, "f16": o.DTYPE_F16, "f8": o.DTYPE_F8E4M3},
             {"row": o.ROW_MAJOR, "col": o.COL_MAJOR},
             {"none": o.EPI_NONE, "bias": o.EPI_BIAS, "bias_relu": o.EPI_BIAS_RELU,
              "bias_gelu_erf": o.EPI_BIAS_GELU_ERF, "bias_gelu_tanh": o.EPI_BIAS_GELU_TANH,
@@ -40,11 +40,11 @@ def oracle_problem(o, w: wl.Workload, lda=0, ldb=0, stride_a=0, stride_b=0, stri
 
 def gpu_desc(g, w: wl.Workload, out_dtype=None, layout_c="row", lda=0, ldb=0, ldc=0,
              stride_a=0, stride_b=0, stride_c=0, stride_bias=0):
-    dt = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16}
+    dt = {"f32": g.F32, "bf16": g.BF16, "f16": g.F16, "f8": g.F8E4M3}
     lay = {"row": g.ROW_MAJOR, "col": g.COL_MAJOR}
     return g.GemmDesc(w.M, w.N, w.K, dtype=dt[w.dtype], layout_a=lay[w.layout_a],
                       layout_b=lay[w.layout_b], layout_c=lay[layout_c], lda=lda, ldb=ldb, ldc=ldc,
-                      dtype_c=dt[out_dtype or w.dtype], epilogue=g.EPILOGUES[w.epilogue],
+                      dtype_c=dt[out_dtype or w.out_dtype or w.dtype], epilogue=g.EPILOGUES[w.epilogue],
                       batch=w.batch, stride_a=stride_a, stride_b=stride_b, stride_c=stride_c,
                       stride_bias=stride_bias, scale=w.scale)
 
@@ -54,6 +54,10 @@ def pad_minor(t: torch.Tensor, pad: int, fill=float("nan")) -> torch.Tensor:
     if pad == 0:
         return t
     b, major, minor = t.shape
+    if t.dtype == torch.float8_e4m3fn:          # no fill / slice assignment for 8-bit floats: go through fp32
+        out = torch.full((b, major, minor + pad), fill, dtype=torch.float32)
+        out[:, :, :minor] = t.float()
+        return out.to(t.dtype)
     out = torch.full((b, major, minor + pad), fill, dtype=t.dtype)
     out[:, :, :minor] = t
     return out
@@ -70,7 +74,7 @@ def run_gpu(g, w: wl.Workload, A: torch.Tensor, B: torch.Tensor, bias, config=-1
     lda, ldb = Ap.shape[2], Bp.shape[2]
     c_major, c_minor = (w.M, w.N) if layout_c == "row" else (w.N, w.M)
     ldc = c_minor + pad_c
-    odt = wl.TORCH_DTYPE[out_dtype or w.dtype]
+    odt = wl.TORCH_DTYPE[out_dtype or w.out_dtype or w.dtype]
     sentinel = -777.0
     Cd = torch.full((w.batch, c_major, ldc), sentinel, dtype=odt, device=dev)
     Ad, Bd = Ap.to(dev), Bp.to(dev)
@@ -114,7 +118,7 @@ def e2_bound(w: wl.Workload, ref, out_dtype=None):
         lip, mag = 1.0, 1.0
     acc = w.K * U32 * s
     epi = 16 * U32 * mag * (np.abs(t) + 1.0) if w.epilogue != "none" else 0.0
-    rnd = OUT_ROUNDOFF[out_dtype or w.dtype] * (np.abs(y) + lip * acc + epi) * 1.001
+    rnd = OUT_ROUNDOFF[out_dtype or w.out_dtype or w.dtype] * (np.abs(y) + lip * acc + epi) * 1.001
     return lip * acc + epi + rnd + 1e-30
 
 

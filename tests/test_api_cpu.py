@@ -159,7 +159,14 @@ def test_descriptor_validation(g):
     assert _status(g, **ok, epilogue=g.EPI_RELU, scale=float("nan")) == 0
     assert "scale" in g.gemm_status_string(-10)
     assert _status(g, **ok, layout_a=2) == -8
-    assert _status(g, **ok, dtype=3) == -8
+    assert _status(g, **ok, dtype=4) == -8
+    # 8-bit E4M3 operands: results are bf16 or fp32; only the matrix-core kernels take them
+    assert _status(g, **ok, dtype=g.F8E4M3) == 0
+    assert _status(g, **ok, dtype=g.F8E4M3, dtype_c=g.F32) == 0
+    assert _status(g, **ok, dtype=g.F8E4M3, dtype_c=g.F8E4M3) == -4
+    assert _status(g, **ok, dtype=g.F8E4M3, dtype_c=g.F16) == -4
+    assert _status(g, M=64, N=64, K=72, dtype=g.F8E4M3) == -4          # K not a multiple of 16
+    assert _status(g, **ok, dtype=g.F8E4M3, layout_b=g.ROW_MAJOR) == -4
     assert _status(g, M=1 << 31, N=64, K=64) == -2
 
 
@@ -203,6 +210,8 @@ def test_kernel_choice(g):
         assert "kernel=skinnystage_d2_b512" in kernel(M=m, N=8192, K=8192)
         assert "kernel=skinnystage_d3_b256" in kernel(M=m, N=28672, K=8192)
     assert "grid=256,1,1" in kernel(M=1, N=8192, K=8192)
+    assert "kernel=mfma8_256x256x128" in kernel(M=8192, N=8192, K=8192, dtype=g.F8E4M3)
+    assert "kernel=mfma8_" in kernel(M=4, N=8192, K=8192, dtype=g.F8E4M3)      # no skinny fp8 kernel
     assert "kernel=simt" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
     # 16-bit operands the tiled kernels cannot take go to the general kernel
     assert "kernel=simt" in kernel(M=256, N=256, K=256, layout_a=g.COL_MAJOR)

@@ -31,7 +31,7 @@ def cfg_index(g, name):
 
 
 def mfma_configs(g):
-    return [n for n in g.config_names() if n.startswith("mfma")]
+    return [n for n in g.config_names() if n.startswith("mfma_")]
 
 
 def skinny_configs(g, m):
@@ -351,7 +351,7 @@ def test_tuner_times_every_applicable_configuration(g, oracle):
     names = g.config_names()
     assert names[best] in times and times[names[best]] == min(times.values())
     assert all(t > 0 for t in times.values())
-    assert {n for n in names if n.startswith("mfma") or n.startswith("simt")} == set(times)   # M = 300: no skinny
+    assert {n for n in names if n.startswith("mfma_") or n.startswith("simt")} == set(times)   # M = 300: no skinny, no fp8
     plan = g.gemm_create_config(desc, best)
     g.gemm_run(plan, Ad, Bd, Cd, bd)
     torch.cuda.synchronize()
@@ -378,7 +378,8 @@ def test_full_size_workloads_on_sampled_outputs(g, oracle, name):
                                  None if bias is None else bias.numpy(), pb, pi, pj, want=("y", "t", "s"))
     got = wl.to_float64(C)[pb, pi, pj]
     err = np.abs(got - ref["y"])
-    scale = w.K * float(A.abs().max()) * float(B.abs().max()) + (float(bias.abs().max()) if bias is not None else 0.0)
+    scale = w.K * float(A.float().abs().max()) * float(B.float().abs().max()) + \
+        (float(bias.abs().max()) if bias is not None else 0.0)
     assert np.isfinite(got).all()
     assert err.max() / scale <= E1_TOL[w.dtype]
     assert np.all(err <= e2_bound(w, ref)), float((err / e2_bound(w, ref)).max())
@@ -411,7 +412,7 @@ def run_splitk(g, w, A, B, bias, splits, out_dtype=None, layout_c="row", pad_c=0
     from helpers import gpu_desc
     c_major, c_minor = (w.M, w.N) if layout_c == "row" else (w.N, w.M)
     ldc = c_minor + pad_c
-    odt = wl.TORCH_DTYPE[out_dtype or w.dtype]
+    odt = wl.TORCH_DTYPE[out_dtype or w.out_dtype or w.dtype]
     Cd = torch.full((1, c_major, ldc), -777.0, dtype=odt, device=dev)
     plan = g.gemm_create_splitk(gpu_desc(g, w, out_dtype, layout_c, ldc=ldc), splits)
     info = plan.info()
@@ -484,3 +485,98 @@ def test_splitk_full_size_against_plain_plan_and_oracle_samples(g, oracle):
     C1 = run_gpu(g, w, A, B, None)
     d = (C.double() - C1.double()).abs().max().item()
     assert d <= 2.0 ** -7 * C1.double().abs().max().item()
+
+
+# ---- fp8 (E4M3) operands ----------------------------------------------------------------------
+
+F8_CONFIGS = ["mfma8_256x256x128_w2x4_s2", "mfma8_128x128x128_w2x2_s2"]
+
+
+def test_f8_exact_integers_ragged_shapes_and_k_tails(g, oracle):
+    """Integers in [-4, 4] are exact in E4M3 and so is everything computed from them: bit-exact
+    results for ragged M and N, K below one slab, K with a tail of 1..7 sixteen-byte pieces, padded
+    rows, fp32 and bf16 output, bias + ReLU."""
+    for cfg in F8_CONFIGS:
+        for (M, N, K) in [(300, 260, 16), (70, 90, 112), (257, 129, 128), (130, 70, 144), (256, 256, 400),
+                          (33, 500, 1040)]:
+            w = wl.Workload("t", M, N, K, dtype="f8", out_dtype="f32", epilogue="bias_relu")
+            sa, sb = wl.operand_shapes(w)
+            A = wl.small_integers(sa, 3, -4, 4, "f8")
+            B = wl.small_integers(sb, 4, -4, 4, "f8")
+            bias = wl.small_integers((N,), 5, -3, 3, "f32")
+            want = torch.relu(A[0].double() @ B[0].double().T + bias.double())
+            say(f"f8 exact {cfg} {M}x{N}x{K}")
+            C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg), pad_a=16, pad_b=32, pad_c=4)
+            assert torch.equal(C[0].double(), want), (cfg, M, N, K)
+    # all ones: every k counted once (8192 is exact in bf16)
+    for cfg in F8_CONFIGS:
+        for K in (128, 256, 8192):
+            w = wl.Workload("t", 130, 70, K, dtype="f8", out_dtype="bf16")
+            ones_a = torch.ones((1, 130, K)).to(torch.float8_e4m3fn)
+            ones_b = torch.ones((1, 70, K)).to(torch.float8_e4m3fn)
+            C = run_gpu(g, w, ones_a, ones_b, None, config=cfg_index(g, cfg))
+            assert torch.all(C.float() == float(K)), (cfg, K)
+
+
+def test_f8_one_hot_k_sweep(g):
+    """A[i, k0] = 1 only: C[i, :] = B[:, k0] exactly, k0 over the chunk, MFMA-step and slab seams."""
+    K = 400
+    ks = [0, 1, 15, 16, 31, 32, 33, 47, 48, 63, 64, 65, 95, 96, 127, 128, 129, 191, 192, 255, 256, 319, 383, 384, 399]
+    for cfg in F8_CONFIGS:
+        M, N = 300, 140
+        w = wl.Workload("t", M, N, K, dtype="f8", out_dtype="f32", seed_b=77)
+        A = wl.one_hot_columns(M, K, ks, "f8").unsqueeze(0)
+        B = wl.small_integers((1, N, K), 9, -4, 4, "f8")
+        say(f"f8 one-hot {cfg}")
+        C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg))
+        for i in range(M):
+            assert torch.equal(C[0, i].double(), B[0, :, ks[i % len(ks)]].double()), (cfg, i)
+
+
+@pytest.mark.parametrize("epilogue", ["none", "bias_gelu_erf", "bias_swish_scale"])
+def test_f8_random_against_oracle(g, oracle, epilogue):
+    for cfg, (M, N, K) in [(F8_CONFIGS[0], (300, 520, 1168)), (F8_CONFIGS[1], (130, 140, 272)), (None, (64, 200, 4096))]:
+        w = wl.Workload("t", M, N, K, dtype="f8", out_dtype="bf16", dist_a=("normal", 1.0),
+                        dist_b=("normal", 1.5 / np.sqrt(K)), epilogue=epilogue, scale=2.0,
+                        dist_bias=("uniform", 1.0), seed_a=41, seed_b=42, seed_bias=43)
+        A, B, bias = wl.make_inputs(w)
+        ref = run_oracle(oracle, w, A, B, bias)
+        for od in ("bf16", "f32"):
+            say(f"f8 random {epilogue} cfg={cfg} {M}x{N}x{K} out={od}")
+            C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg) if cfg else -1, out_dtype=od)
+            r = assert_parity(w, C, ref, A.float(), B.float(), bias, out_dtype=od)
+            say("   ", r)
+
+
+def test_f8_batches_and_splitk(g, oracle):
+    w = wl.Workload("t", 96, 136, 256, dtype="f8", out_dtype="bf16", batch=3, seed_a=51, seed_b=52)
+    A, B, _ = wl.make_inputs(w)
+    C = run_gpu(g, w, A, B, None)
+    assert_parity(w, C, run_oracle(oracle, w, A, B, None), A.float(), B.float(), None)
+    w2 = wl.Workload("t", 200, 136, 4096, dtype="f8", out_dtype="bf16", dist_b=("normal", 1.0 / 64), seed_a=53, seed_b=54)
+    A2, B2, _ = wl.make_inputs(w2)
+    ref = run_oracle(oracle, w2, A2, B2, None)
+    for splits in (4, 0):
+        C2, info = run_splitk(g, w2, A2, B2, None, splits)
+        say("   ", info)
+        assert "mfma8" in info
+        assert_parity(w2, C2, ref, A2.float(), B2.float(), None)
+
+
+def test_k_tail_every_length_on_every_mfma_tile(g):
+    """K tails of every length (1 .. all k-steps of a slab), alone and after one full slab, on
+    every matrix-core tile shape, integer data, fp32 output: bit exact.  (A tail that fills all
+    k-steps ends with MFMAs right before the epilogue reads the accumulators.)"""
+    for cfg in mfma_configs(g) + F8_CONFIGS:
+        f8 = cfg.startswith("mfma8")
+        dt, piece, slab = ("f8", 16, 128) if f8 else ("bf16", 8, 64)
+        if cfg.startswith("mfma_256x256x32"):
+            slab = 32
+        for K in [p for p in range(piece, slab, piece)] + [slab + p for p in range(piece, slab, piece)]:
+            w = wl.Workload("t", 130, 132, K, dtype=dt, out_dtype="f32")
+            sa, sb = wl.operand_shapes(w)
+            A = wl.small_integers(sa, 3, -3, 3, dt)
+            B = wl.small_integers(sb, 4, -3, 3, dt)
+            C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg))
+            assert torch.equal(C[0].double(), A[0].double() @ B[0].double().T), (cfg, K)
+        say(f"k tails {cfg}: ok")

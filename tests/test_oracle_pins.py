@@ -389,6 +389,33 @@ def test_f16_decode_exhaustive(oracle):
         assert (math.isnan(got) and math.isnan(want[b])) or got == want[b]
 
 
+def test_f8e4m3_decode_exhaustive_and_products(oracle):
+    """All 256 codes of OCP E4M3: the format's defining values by hand (1 = 0x38, largest 448 = 0x7E,
+    smallest subnormal 2^-9 = 0x01, smallest normal 2^-6 = 0x08, NaN only at S.1111.111, no
+    infinity), monotone in the code for each sign, and equal to the library's decoding; then a
+    small product with fp8 operands against exact integer arithmetic."""
+    val = [oracle.f8e4m3_bits_to_double(c) for c in range(256)]
+    assert val[0x00] == 0.0 and val[0x80] == 0.0 and math.copysign(1.0, val[0x80]) == -1.0
+    assert val[0x38] == 1.0 and val[0xB8] == -1.0 and val[0x40] == 2.0 and val[0x3C] == 1.5
+    assert val[0x7E] == 448.0 and val[0x78] == 256.0 and val[0x77] == 240.0
+    assert val[0x01] == 2.0 ** -9 and val[0x07] == 7 * 2.0 ** -9 and val[0x08] == 2.0 ** -6
+    assert math.isnan(val[0x7F]) and math.isnan(val[0xFF])
+    assert all(math.isfinite(v) for c, v in enumerate(val) if c & 0x7F != 0x7F)
+    pos = val[0:0x7F]
+    assert all(a < b for a, b in zip(pos, pos[1:]))
+    assert all(val[c | 0x80] == -val[c] for c in range(0x7F))
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.nan_to_num(lib, nan=1e9), np.nan_to_num(np.array(val), nan=1e9))
+    # 3 x 4 x 5 product of small integers stored as fp8, column-major B (K contiguous)
+    rng = np.random.default_rng(3)
+    A = rng.integers(-4, 5, (3, 5)); B = rng.integers(-4, 5, (4, 5))
+    a8 = torch.from_numpy(A.astype(np.float32)).to(torch.float8_e4m3fn)
+    b8 = torch.from_numpy(B.astype(np.float32)).to(torch.float8_e4m3fn)
+    p = oracle.Problem(3, 4, 5, oracle.DTYPE_F8E4M3, oracle.DTYPE_F8E4M3)
+    y = oracle.ref_gemm(p, wl.storage_numpy(a8), wl.storage_numpy(b8))["y"][0]
+    assert np.array_equal(y, (A @ B.T).astype(np.float64))
+
+
 def test_bf16_round_to_nearest_even(oracle):
     """Ties: 1 + 2^-8 -> 1.0 ; 1 + 3*2^-8 -> 1 + 2^-6 ; round trip of every
     finite pattern; agreement with the library cast used by the generators."""

@@ -19,7 +19,8 @@ from typing import Optional, Tuple
 import numpy as np
 import torch
 
-TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16,
+               "f8": torch.float8_e4m3fn}     # OCP E4M3: operands only, results are bf16 or fp32
 
 
 @dataclass(frozen=True)
@@ -33,7 +34,8 @@ class Workload:
     M: int
     N: int
     K: int
-    dtype: str = "bf16"            # storage type of A, B and C
+    dtype: str = "bf16"            # storage type of A, B and C ("f8": A and B only, C is out_dtype)
+    out_dtype: Optional[str] = None   # storage type of C when it differs from dtype
     layout_a: str = "row"
     layout_b: str = "col"
     dist_a: Tuple[str, float] = ("normal", 1.0)
@@ -56,7 +58,8 @@ class Workload:
     def bytes(self) -> float:
         """Compulsory traffic: read A and B once, write C once (bias ignored)."""
         e = torch.empty((), dtype=TORCH_DTYPE[self.dtype]).element_size()
-        return float(e * self.batch * (self.M * self.K + self.K * self.N + self.M * self.N))
+        ec = torch.empty((), dtype=TORCH_DTYPE[self.out_dtype or self.dtype]).element_size()
+        return float(self.batch * (e * (self.M * self.K + self.K * self.N) + ec * self.M * self.N))
 
     @property
     def has_bias(self) -> bool:
@@ -97,6 +100,11 @@ WORKLOADS = {w.name: w for w in [
     Workload("sigres_8192x16384x4096", 8192, 16384, 4096, dist_a=("normal", _k(4096)),
              dist_b=("normal", 1.5 * _k(4096)), epilogue="bias_sigmoid_scale_residual", scale=0.5,
              dist_bias=("uniform", 1.0), seed_a=5021, seed_b=5022, seed_bias=5023),
+    # 8-bit floating-point operands (E4M3), bf16 result: the square shape and an LLM layer shape
+    Workload("f8_square_8192", 8192, 8192, 8192, dtype="f8", out_dtype="bf16", dist_a=("normal", 1.0),
+             dist_b=("normal", 1.0), seed_a=8001, seed_b=8002),
+    Workload("f8_llm_4096x14336x4096", 4096, 14336, 4096, dtype="f8", out_dtype="bf16", dist_a=("normal", 1.0),
+             dist_b=("normal", 0.25), seed_a=8003, seed_b=8004),
     # few output tiles, long K: the split-K case
     Workload("smallmn_512x512x32768", 512, 512, 32768, dist_a=("normal", 1.0),
              dist_b=("normal", _k(32768)), seed_a=6001, seed_b=6002),
@@ -215,6 +223,8 @@ def storage_numpy(t: Optional[torch.Tensor]):
         return t.numpy().reshape(-1)
     if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16).reshape(-1)
+    if t.dtype == torch.float8_e4m3fn:
+        return t.view(torch.uint8).numpy().reshape(-1)
     raise TypeError(t.dtype)
 
 
