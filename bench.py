@@ -154,10 +154,11 @@ def measured_peak(g, dev, bound, dtype):
     loop for the matrix-core bound, a streaming read of 1.25 GiB for the HBM bound.  None for the
     other bounds."""
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
-    if bound == "mfma" and dtype in ("bf16", "f16"):
-        code = g.F16 if dtype == "f16" else g.BF16
+    if bound == "mfma" and dtype in ("bf16", "f16", "f8"):
+        code = {"f16": g.F16, "f8": g.F8E4M3}.get(dtype, g.BF16)
         return {"value": round(g.probe_mfma_peak(code, sink, min_seconds=0.3), 1), "unit": "TFLOP/s",
-                "what": "v_mfma_f32_32x32x16 register loop, 8 waves per CU, fixed pseudo-random operands",
+                "what": ("v_mfma_f32_32x32x64_f8f6f4" if dtype == "f8" else "v_mfma_f32_32x32x16") +
+                        " register loop, 8 waves per CU, fixed pseudo-random operands",
                 "value_fresh_operands": round(g.probe_mfma_peak(code, sink, min_seconds=0.3, refresh_operands=True), 1)}
     if bound == "hbm":
         n = 5 << 28

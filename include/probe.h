@@ -21,7 +21,7 @@ extern "C" {
 
 /*
  * probe_mfma_peak - every CU runs 8 waves of v_mfma_f32_32x32x16 (dtype GEMM_BF16 or
- * GEMM_F16) on register operands with pseudo-random signs and significands (magnitude about
+ * GEMM_F16) or v_mfma_f32_32x32x64_f8f6f4 (GEMM_F8E4M3) on register operands with pseudo-random signs and significands (magnitude about
  * 2^-6), the accumulator footprint of the 256x256 GEMM tile (8 independent 32x32
  * accumulators per wave), no memory traffic.  refresh_operands = 0: the same six operand
  * registers are re-used in rotation (the classic peak loop); 1: their sign and significand

@@ -39,6 +39,16 @@ template <> struct ProbeMfma<f16_t> {
   }
 };
 
+// fp8 (E4M3): operands of 8 registers, v_mfma_f32_32x32x64_f8f6f4
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
+struct ProbeMfma8 {
+  static constexpr uint32_t kFlipMask = 0x87878787u;       // sign and significand bits of the four bytes
+  static __device__ __forceinline__ uint32_t word(uint32_t r) { return (r & kFlipMask) | 0x28282828u; }  // 2^-2 ..
+  static __device__ __forceinline__ void run(const i32x8_t& a, const i32x8_t& b, f32x16acc& c) {
+    c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);   // fp8 x fp8, no block scales
+  }
+};
+
 __device__ __forceinline__ uint32_t mix(uint32_t x) {      // integer hash (xorshift-multiply)
   x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
   return x;
@@ -101,6 +111,57 @@ __global__ __launch_bounds__(512) void mfma_peak_kernel(int steps, float* sink) 
   if (t == 1.2345e38f) *sink = t;                        // never true; keeps the loop alive
 }
 
+template <bool REFRESH>
+__global__ __launch_bounds__(512) void mfma8_peak_kernel(int steps, float* sink) {
+  i32x8_t a[4], b[2];
+  const uint32_t id = (blockIdx.x * 512u + threadIdx.x) * 64u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[i][e] = (int)ProbeMfma8::word(mix(id + i * 8 + e));
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[i][e] = (int)ProbeMfma8::word(mix(id + 32 + i * 8 + e));
+  f32x16acc acc[4][2];
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.0f;
+  uint32_t rnd = 0x9e3779b9u;
+  for (int s = 0; s < steps; s += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (REFRESH) {
+        rnd = rnd * 1664525u + 1013904223u;
+        const int flip = (int)(rnd & ProbeMfma8::kFlipMask);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a[i][e] ^= flip;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) b[i][e] ^= (int)(((uint32_t)flip >> 1) & ProbeMfma8::kFlipMask);
+      }
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < 2; ++n) ProbeMfma8::run(b[(n + u) & 1], a[(m + u) & 3], acc[m][n]);
+    }
+  }
+  float t = 0.0f;
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int n = 0; n < 2; ++n)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t += acc[m][n][r];
+  if (t == 1.2345e38f) *sink = t;
+}
+
 // a wave reads whole 16 KB pieces, 16 loads of 16 bytes per lane in flight
 __global__ __launch_bounds__(256) void read_peak_kernel(const u32x4_t* __restrict__ src, int64_t pieces,
                                                         float* sink) {
@@ -152,7 +213,7 @@ int timed(F launch, hipStream_t s, double min_seconds, double* sec_per_launch) {
 extern "C" int probe_mfma_peak(int dtype, int refresh_operands, void* sink, void* hip_stream,
                                double min_seconds, double* tflops) {
   if (!sink || !tflops) return GEMM_ERR_NULL;
-  if (dtype != GEMM_BF16 && dtype != GEMM_F16) return GEMM_ERR_UNSUPPORTED;
+  if (dtype != GEMM_BF16 && dtype != GEMM_F16 && dtype != GEMM_F8E4M3) return GEMM_ERR_UNSUPPORTED;
   if (refresh_operands != 0 && refresh_operands != 1) return GEMM_ERR_BAD_ENUM;
   if ((uintptr_t)sink & 3) return GEMM_ERR_MISALIGNED;
   if (!(min_seconds >= 0.0)) min_seconds = 0.0;
@@ -162,6 +223,15 @@ extern "C" int probe_mfma_peak(int dtype, int refresh_operands, void* sink, void
   const int steps = 4096, grid = 256;                               // ~0.3 ms per launch
   double sec = 0;
   float* sk = (float*)sink;
+  if (dtype == GEMM_F8E4M3) {
+    if (!refresh_operands)
+      rc = timed([&] { mfma8_peak_kernel<false><<<grid, 512, 0, s>>>(steps, sk); }, s, min_seconds, &sec);
+    else
+      rc = timed([&] { mfma8_peak_kernel<true><<<grid, 512, 0, s>>>(steps, sk); }, s, min_seconds, &sec);
+    if (rc != GEMM_OK) return rc;
+    *tflops = 2.0 * 32 * 32 * 64 * kMfmaPerStep * (double)steps * 8.0 * grid / sec / 1e12;
+    return GEMM_OK;
+  }
   if (dtype == GEMM_BF16 && !refresh_operands)
     rc = timed([&] { mfma_peak_kernel<bf16_t, false><<<grid, 512, 0, s>>>(steps, sk); }, s, min_seconds, &sec);
   else if (dtype == GEMM_BF16)

@@ -49,6 +49,7 @@ def test_binding_exposes_the_same_names(g):
 def test_probe_argument_checks_need_no_device(g):
     for call, want in [(lambda: g.probe_mfma_peak(g.BF16, 0, stream=0), -1),
                        (lambda: g.probe_mfma_peak(g.F32, 0x1000, stream=0), -4),
+                       (lambda: g.probe_mfma_peak(7, 0x1000, stream=0), -4),
                        (lambda: g.probe_mfma_peak(g.BF16, 0x1002, stream=0), -5),
                        (lambda: g.probe_read_peak(0, 1 << 30, 0x1000, stream=0), -1),
                        (lambda: g.probe_read_peak(0x10000, 1 << 20, 0x1000, stream=0), -2),      # too small

@@ -14,6 +14,9 @@ def test_probes_report_plausible_peaks():
         for refresh in (False, True):
             t = g.probe_mfma_peak(code, sink, min_seconds=0.1, refresh_operands=refresh)
             assert 500.0 < t <= 2516.6 * 1.02, t       # never above the nominal matrix-core peak
+    for refresh in (False, True):
+        t = g.probe_mfma_peak(g.F8E4M3, sink, min_seconds=0.1, refresh_operands=refresh)
+        assert 1000.0 < t <= 5033.2 * 1.02, t
     n = 1 << 30
     buf = torch.ones(n, dtype=torch.uint8, device=dev)
     r = g.probe_read_peak(buf, n, sink, min_seconds=0.1)
