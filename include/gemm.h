@@ -101,6 +101,18 @@ typedef struct {
 } gemm_desc_t;
 
 /*
+ * Which kernel serves a problem.  The matrix-core and skinny kernels take 16-bit (or fp8)
+ * operands with K contiguous in both (A row-major, B column-major: the weight matrix stored
+ * N x K), row-major C, and move 16-byte pieces: K, lda, ldb and the batch strides of A and B
+ * must be multiples of 16 bytes' worth of elements (8 for bf16 / fp16, 16 for fp8), and at
+ * gemm_run A and B must be 16-byte aligned (GEMM_ERR_MISALIGNED otherwise).  M <= 16 goes to
+ * the HBM-bound skinny kernels, everything else to the tiled MFMA kernel.  Every other
+ * combination (fp32 operands, other layouts, odd leading dimensions) is served by the general
+ * fp32-FMA kernel, which needs element alignment only; fp8 operands have no such fallback
+ * (GEMM_ERR_UNSUPPORTED).
+ */
+
+/*
  * gemm_create - validate a descriptor and choose kernel, tile shape and grid.
  * Runs entirely on the host and touches no device.  On success *out_plan
  * receives a new plan (release with gemm_destroy); on failure it is set to NULL
