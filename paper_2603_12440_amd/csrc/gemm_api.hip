@@ -173,7 +173,7 @@ hipError_t launch_skinny_ring(const gemm_plan& pl, const void* A, const void* B,
   return hipGetLastError();
 }
 
-template <typename T, int DEPTH, int RB>
+template <typename T, int DEPTH, int RB, int WAVES>
 hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B, void* C,
                                const void* bias, hipStream_t s) {
   const gemm_desc_t& d = pl.d;
@@ -187,7 +187,7 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
   a.act = epilogue_activation(d.epilogue);
   a.scale = d.scale;
   a.y_f32 = d.dtype_c == GEMM_F32;
-  skinny_stage_kernel<T, DEPTH, RB><<<pl.grid, pl.block, 0, s>>>(a);
+  skinny_stage_kernel<T, DEPTH, RB, WAVES><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
 
@@ -224,7 +224,10 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
 // skinny with W staged through registers into wave-private LDS slabs: same panel shape
 #define SKINNY_STAGE_CFG(DEPTH, RB)                                                        \
   { "skinnystage_d" #DEPTH "_b" #RB, KIND_SKINNY_RING, 16, 32, RB / 2, 256, 4 * 48 * RB,     \
-    { nullptr, launch_skinny_stage<bf16_t, DEPTH, RB>, launch_skinny_stage<f16_t, DEPTH, RB> } }
+    { nullptr, launch_skinny_stage<bf16_t, DEPTH, RB, 4>, launch_skinny_stage<f16_t, DEPTH, RB, 4> } }
+#define SKINNY_STAGE8_CFG(DEPTH, RB)                                                       \
+  { "skinnystage_d" #DEPTH "_b" #RB "_w8", KIND_SKINNY_RING, 16, 32, RB / 2, 512, 8 * 48 * RB, \
+    { nullptr, launch_skinny_stage<bf16_t, DEPTH, RB, 8>, launch_skinny_stage<f16_t, DEPTH, RB, 8> } }
 // skinny through wave-private LDS rings: bm = 16 x rows, bn = 32 rows of W per workgroup
 #define SKINNY_RING_CFG(NS)                                                                \
   { "skinnyring_s" #NS, KIND_SKINNY_RING, 16, 32, 64, 256, 4 * NS * 6144,                   \
@@ -246,6 +249,10 @@ const Config kConfigs[] = {
     SKINNY_CFG(2, 4, 1),
     SKINNY_CFG(4, 4, 1),
     SKINNY_CFG(8, 4, 1),
+    SKINNY_CFG(1, 8, 1),
+    SKINNY_CFG(1, 8, 2),
+    SKINNY_CFG(2, 8, 1),
+    SKINNY_CFG(4, 8, 1),
     SKINNY_MFMA_CFG(1, 8),
     SKINNY_MFMA_CFG(1, 16),
     SKINNY_MFMA_CFG(2, 8),
@@ -255,6 +262,7 @@ const Config kConfigs[] = {
     SKINNY_STAGE_CFG(2, 256),
     SKINNY_STAGE_CFG(3, 256),
     SKINNY_STAGE_CFG(2, 512),
+    SKINNY_STAGE8_CFG(2, 256),
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -414,11 +422,17 @@ int choose(const gemm_desc_t& d) {
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
   if (d.M <= 4) {
+    // two waves per SIMD (8 per workgroup, one workgroup per CU) stream faster than one; for
+    // long weight matrices two such workgroups per CU are a little better still (M = 1)
+    const char* name = d.M == 1 ? (d.N >= 16384 ? "skinny_m1_w8_g2" : "skinny_m1_w8_g1")
+                       : d.M == 2 ? "skinny_m2_w8_g1" : "skinny_m4_w8_g1";
+    const int i = find_config(name);
+    if (i >= 0 && applicable(kConfigs[i], d)) return i;
     int best = -1;
-    for (int i = 0; i < kNumConfigs; ++i)
-      if (kConfigs[i].kind == KIND_SKINNY && applicable(kConfigs[i], d) &&
-          (best < 0 || kConfigs[i].bm < kConfigs[best].bm))
-        best = i;
+    for (int q = 0; q < kNumConfigs; ++q)
+      if (kConfigs[q].kind == KIND_SKINNY && applicable(kConfigs[q], d) &&
+          (best < 0 || kConfigs[q].bm < kConfigs[best].bm))
+        best = q;
     if (best >= 0) return best;
   }
   const int best = best_mfma(d, nullptr);

@@ -486,23 +486,24 @@ __global__ __launch_bounds__(256) void skinny_ring_kernel(SkinnyArgs p) {
 }
 
 // ---- M up to 16, W staged through registers ------------------------------------------
-// Same division of work as the ring kernel (a workgroup owns 32 rows of W, its four
-// waves split K into quarters, one 32x32x16 MFMA tile per wave, quarters added at the
-// end), but W and x travel global -> registers -> LDS: plain 16-byte loads in which 16
+// Same division of work as the ring kernel (a workgroup owns 32 rows of W, its four or
+// eight waves split K into equal parts, one 32x32x16 MFMA tile per wave, the parts added
+// at the end; eight waves = two per SIMD stream faster when there is one workgroup per CU), but W and x travel global -> registers -> LDS: plain 16-byte loads in which 16
 // (or 32) lanes cover 256 (512) contiguous bytes of a row, DEPTH slabs requested ahead,
 // then ds_write_b128 into one wave-private, swizzled LDS slab from which the MFMA
 // fragments are read back.  For a stream that comes from HBM this moves more bytes per
 // microsecond than direct-to-LDS loads do.
-template <typename T, int DEPTH, int RB>
-__global__ __launch_bounds__(256) void skinny_stage_kernel(SkinnyArgs p) {
+template <typename T, int DEPTH, int RB, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void skinny_stage_kernel(SkinnyArgs p) {
   constexpr int kRowBytes = RB;                        // RB/2 columns per slab: 256 or 512 bytes of each row
   constexpr int kCols = RB / 2;
   constexpr int kWBytes = 32 * kRowBytes, kXBytes = 16 * kRowBytes;
   constexpr int kLPR = RB / 16, kRPI = 64 / kLPR;      // lanes per row, rows per load instruction
   constexpr int kWLoads = 32 / kRPI, kXLoads = 16 / kRPI;   // 16-byte loads per lane and slab
   constexpr int kSteps = kCols / 16;                   // MFMAs per slab
-  static_assert(4 * (kWBytes + kXBytes) >= 4 * 16 * 64 * 4, "the slabs double as the reduction buffer");
-  __shared__ __attribute__((aligned(1024))) unsigned char slabs[4 * (kWBytes + kXBytes)];
+  static_assert(WAVES == 4 || WAVES == 8, "K is split over four or eight waves");
+  static_assert(kWBytes + kXBytes >= 16 * 64 * 4, "the slabs double as the reduction buffer");
+  __shared__ __attribute__((aligned(1024))) unsigned char slabs[WAVES * (kWBytes + kXBytes)];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -569,8 +570,8 @@ __global__ __launch_bounds__(256) void skinny_stage_kernel(SkinnyArgs p) {
     }
   };
 
-  const int s_full = p.K / kCols;                        // full slabs, split over the four waves
-  const int per_wave = (s_full + 3) / 4;
+  const int s_full = p.K / kCols;                        // full slabs, split over the waves
+  const int per_wave = (s_full + WAVES - 1) / WAVES;
   const int s_begin = min(wave * per_wave, s_full);
   const int s_end = min(s_full, s_begin + per_wave);
   int s = s_begin;
@@ -606,7 +607,7 @@ __global__ __launch_bounds__(256) void skinny_stage_kernel(SkinnyArgs p) {
       }
     }
   }
-  if (wave == 3 && s_full * kCols < p.K) {
+  if (wave == WAVES - 1 && s_full * kCols < p.K) {
     // K tail: chunks past K are written as zeros
     const bool live = s_full * kCols + lc * 8 < p.K;
     const int64_t off = (int64_t)s_full * kRowBytes;
@@ -626,20 +627,22 @@ __global__ __launch_bounds__(256) void skinny_stage_kernel(SkinnyArgs p) {
 
   // add the four K quarters (the slabs are free now), then bias, activation, store
   __syncthreads();
-  float* red = (float*)slabs;                          // [4 waves][16 regs][64 lanes]
+  float* red = (float*)slabs;                          // [WAVES][16 regs][64 lanes]
 #pragma unroll
   for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
   __syncthreads();
-  // wave w finishes accumulator registers 4w .. 4w+3: x rows 8w + 4*(lane/32) + e, column lane%32
-  // (waves 2 and 3 hold only the repeated rows 16 .. 31 and store nothing)
+  // each wave finishes 16 / WAVES accumulator registers; register r of lane l is x row
+  // 8*(r/4) + 4*(l/32) + r%4, column l%32 (rows 16 .. 31 repeat rows 0 .. 15 and are dropped)
   const int n = n0 + fr;
   const float bv = (bias && n < p.N) ? bias[n] : 0.0f;
+  constexpr int kPerWave = 16 / WAVES;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int r = wave * 4 + e;
-    const float t = red[(0 * 16 + r) * 64 + lane] + red[(1 * 16 + r) * 64 + lane] +
-                    red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
-    const int m = 8 * wave + 4 * fh + e;
+  for (int e = 0; e < kPerWave; ++e) {
+    const int r = wave * kPerWave + e;
+    float t = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) t += red[(w * 16 + r) * 64 + lane];
+    const int m = 8 * (r / 4) + 4 * fh + r % 4;
     if (m < p.M && n < p.N) {
       const float v = apply_activation(p.act, t + bv, p.scale);
       const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;

@@ -207,6 +207,9 @@ def test_kernel_choice(g):
     assert "grid=1024,1,1" in kernel(M=8192, N=8192, K=8192)
     for m in (1, 4):
         assert "kernel=skinny_m" in kernel(M=m, N=8192, K=8192)
+    assert "kernel=skinny_m1_w8_g1" in kernel(M=1, N=8192, K=8192)
+    assert "kernel=skinny_m1_w8_g2" in kernel(M=1, N=28672, K=8192)
+    assert "kernel=skinny_m4_w8_g1" in kernel(M=3, N=8192, K=8192)
     for m in (5, 8, 16):
         assert "kernel=skinnystage_d2_b512" in kernel(M=m, N=8192, K=8192)
         assert "kernel=skinnystage_d3_b256" in kernel(M=m, N=28672, K=8192)

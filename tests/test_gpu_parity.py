@@ -116,7 +116,8 @@ def test_all_ones_gives_K(g, K):
                         (130, 70, "mfma_128x128x64_w2x2_s2"), (1, 96, "skinny_m1_w4_g1"),
                         (8, 33, "skinny_m8_w4_g1"), (16, 33, "skinnymfma_r1_u8"), (9, 70, "skinnymfma_r2_u8"),
                         (16, 70, "skinnyring_s5"), (3, 33, "skinnyring_s6"),
-                        (16, 70, "skinnystage_d3_b256"), (3, 33, "skinnystage_d2_b512"), (9, 64, "skinnystage_d2_b256")]:
+                        (16, 70, "skinnystage_d3_b256"), (3, 33, "skinnystage_d2_b512"), (9, 64, "skinnystage_d2_b256"),
+                        (16, 70, "skinnystage_d2_b256_w8"), (5, 33, "skinnystage_d2_b256_w8")]:
         w = wl.Workload("t", M, N, K)
         say(f"all-ones {M}x{N}x{K} {cfg}")
         A = torch.ones((1, M, K), dtype=torch.bfloat16)
@@ -138,7 +139,9 @@ def test_one_hot_k_sweep_copies_columns_of_b(g):
                                                                 ("skinnyring_s6", 5, 70),
                                                                 ("skinnystage_d2_b512", 16, 100),
                                                                 ("skinnystage_d3_b256", 5, 70),
-                                                                ("skinnystage_d2_b256", 13, 33)]:
+                                                                ("skinnystage_d2_b256", 13, 33),
+                                                                ("skinnystage_d2_b256_w8", 16, 100),
+                                                                ("skinnystage_d2_b256_w8", 7, 33)]:
         w = wl.Workload("t", M, N, K, seed_b=77)
         say(f"one-hot {cfg}")
         A = wl.one_hot_columns(M, K, ks).unsqueeze(0)
@@ -212,7 +215,8 @@ def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
                            (16, 100, 1032, "skinnymfma_r1_u8"), (5, 70, 264, "skinnymfma_r2_u8"),
                            (16, 100, 1032, "skinnyring_s4"), (7, 70, 264, "skinnyring_s6"),
                            (16, 100, 1032, "skinnystage_d3_b256"), (7, 70, 264, "skinnystage_d2_b512"),
-                           (11, 40, 2120, "skinnystage_d2_b256"),
+                           (11, 40, 2120, "skinnystage_d2_b256"), (16, 100, 1032, "skinnystage_d2_b256_w8"),
+                           (6, 70, 3128, "skinnystage_d2_b256_w8"),
                            (70, 90, 50, "simt_64x64x16")]:
         # pre-activations of order 1 so that the activations' curved parts are exercised
         w = wl.Workload("t", M, N, K, dist_a=("normal", 1.0), dist_b=("normal", 1.5 / np.sqrt(K)),
