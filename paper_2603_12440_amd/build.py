@@ -36,14 +36,37 @@ def build_library(verbose: bool = False) -> str:
            # packed-fp32 VALU forms stay off
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-function", "-o", LIB] + SOURCES
+    cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    noise = ("is not a recognized feature for this target", "-Rpass-analysis=kernel-resource-usage")
+    err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
+    bad = kernels_with_scratch(res.stderr)
+    if bad:
+        os.remove(LIB)
+        raise RuntimeError("kernels that keep data in scratch memory (the hand-scheduled kernels place their own "
+                           "waits for asynchronous LDS reads and matrix-core results; a register the compiler "
+                           "moves to memory in between breaks that):\n  " + "\n  ".join(bad))
     return LIB
+
+
+def kernels_with_scratch(remarks: str) -> list:
+    """Names of kernels whose resource-usage remarks show scratch memory or vector-register spills
+    (scalar registers spilled into vector-register lanes stay in registers and are fine)."""
+    bad, name = [], None
+    for line in remarks.splitlines():
+        if "remark:" not in line:
+            continue
+        text = line.split("remark:", 1)[1].strip()
+        if text.startswith("Function Name:"):
+            name = text.split(":", 1)[1].split("[")[0].strip()
+        elif name and text.split(":")[0] in ("ScratchSize [bytes/lane]", "VGPRs Spill"):
+            if int(text.split(":")[1].split("[")[0]) != 0 and name not in bad:
+                bad.append(name)
+    return bad
 
 
 if __name__ == "__main__":

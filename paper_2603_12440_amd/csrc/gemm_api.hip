@@ -213,7 +213,7 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
 // bn = workgroups per CU the grid is sized for
 #define SKINNY_CFG(MB, WAVES, PER_CU)                                                      \
   { "skinny_m" #MB "_w" #WAVES "_g" #PER_CU, KIND_SKINNY, MB, PER_CU, kSkinnyKC,           \
-    64 * WAVES, MB <= 2 ? 16 : MB * kSkinnyKC * 2,                                         \
+    64 * WAVES, (MB == 1 || (MB == 2 && WAVES <= 4)) ? 16 : MB * kSkinnyKC * 2,            \
     { nullptr, launch_skinny<bf16_t, MB, WAVES>, launch_skinny<f16_t, MB, WAVES> } }
 
 // skinny on the matrix cores: bm = 16 x rows, bn = rows of W per workgroup, bk = k per MFMA

@@ -254,18 +254,31 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // "scalar base + 32-bit lane offset" through inline assembly: the slab's base address is
   // wave-uniform, so no vector ALU work is spent on 64-bit addresses in the MFMA stream.
   // M0 carries the LDS destination of the wave (lane l lands at M0 + 16*l).
+  // Every lambda below is forced inline: left to its size heuristics the compiler may keep a
+  // call, and with it the captured accumulators and fragments in memory instead of registers,
+  // which the hand-placed waits and the assembly statements cannot tolerate.
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_uchar_t*)smem;
-  auto issue_one_load = [&](int q, int kt, int stage) {
+  auto issue_one_load = [&](int q, int kt, int stage) __attribute__((always_inline)) {
     const bool is_a = q < Cfg::A_LOADS;
     const int qq = is_a ? q : q - Cfg::A_LOADS;
-    const char* g = (const char*)(is_a ? Ab : Bb) + (int64_t)kt * ROWB;
+    // (wave-uniform by construction; read back through the scalar unit so that the "s" operand
+    // below holds even where the compiler would otherwise carry this address in vector registers)
+    const uint64_t gv = (uint64_t)((const char*)(is_a ? Ab : Bb) + (int64_t)kt * ROWB);
+    // (the builtin returns a signed int: widen each half as unsigned)
+    const uint32_t g_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gv >> 32));
+    const uint32_t g_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gv);
+    const char* g = (const char*)(((uint64_t)g_hi << 32) | (uint64_t)g_lo);
     const uint32_t dst = lds_base + stage * Cfg::STAGE_BYTES + (is_a ? 0 : Cfg::A_BYTES) +
                          (wave * (is_a ? Cfg::A_LOADS : Cfg::B_LOADS) + qq) * 1024;
     const uint32_t off = is_a ? a_off[qq] : b_off[qq];
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    // (s_nop 4: where the compiler had to fetch the address from vector registers just before
+    // this statement, the load must not read the scalar pair earlier than 5 cycles after that
+    // write, and the compiler does not count cycles inside an asm statement; it also covers
+    // the one cycle between the M0 write and its use)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(dst), "v"(off), "s"(g) : "memory", "m0");
   };
-  auto issue_loads = [&](int kt, int stage) {
+  auto issue_loads = [&](int kt, int stage) __attribute__((always_inline)) {
 #pragma unroll
     for (int q = 0; q < Cfg::A_LOADS + Cfg::B_LOADS; ++q) issue_one_load(q, kt, stage);
   };
@@ -273,7 +286,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // K tail: the last slab may hold fewer than BK valid columns.  Chunks past K
   // must read as zero, which a direct-to-LDS load cannot do, so that one slab goes
   // through registers.  (K is a multiple of 8: chunks are never split.)
-  auto issue_loads_tail = [&](int kt, int stage) {
+  auto issue_loads_tail = [&](int kt, int stage) __attribute__((always_inline)) {
     const int kvalid = p.K - kt * BK;                      // valid columns in this slab
     const char* ga = (const char*)Ab + (int64_t)kt * ROWB;
     const char* gb = (const char*)Bb + (int64_t)kt * ROWB;
@@ -328,7 +341,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   typedef StepOrder<MT, NT> Ord;
   const uint32_t smem_base = lds_base;
 
-  auto read_one = [&](int i, int stage, int kk, int buf) {       // i-th read of the fixed read order
+  auto read_one = [&](int i, int stage, int kk, int buf) __attribute__((always_inline)) {       // i-th read of the fixed read order
     const uint32_t s = smem_base + stage * Cfg::STAGE_BYTES;
     const int idx = Ord::t.r_idx[i];
 #pragma unroll
@@ -337,7 +350,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       else lds_read_b128(af[buf][idx][j], s + a_rd[kk][j], idx * (32 * ROWB));
     }
   };
-  auto read_frags = [&](int stage, int kk, int buf) {
+  auto read_frags = [&](int stage, int kk, int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < Ord::kReads; ++i) read_one(i, stage, kk, buf);
   };
@@ -351,7 +364,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // slab `lk` into stage `ls` follow the reads, spread over the remaining MFMAs.
   // Operands go in swapped (B fragment first) so that a lane ends up holding one row
   // of C and runs of 4 consecutive columns: that is what the stores want.
-  auto step = [&](int cur, bool reads, int rs, int rk, bool loads, int lk, int ls) {
+  auto step = [&](int cur, bool reads, int rs, int rk, bool loads, int lk, int ls) __attribute__((always_inline)) {
     constexpr int kLoads = Cfg::A_LOADS + Cfg::B_LOADS;
     constexpr int kLeft = Ord::kMfma > Ord::kReads ? Ord::kMfma - Ord::kReads : 1;
     constexpr int kPer = (kLoads + kLeft - 1) / kLeft;
@@ -382,11 +395,11 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // slab t lives in LDS stage t % NSTAGE.  The hand-over to slab t+1 happens before
   // the last MFMA step of slab t (whose fragments are already in registers), so the
   // barrier and the first fragment reads of slab t+1 hide behind those MFMAs, and
-  // stage t % NSTAGE is refilled with slab t+NSTAGE right after the barrier.  Past
-  // the end the refill re-loads the last full slab into a stage nobody reads again:
-  // every iteration then issues the same number of loads, the wait counts are
-  // constants, and the loop body has no branch in it.  A K tail (K % BK != 0) is
-  // multiplied after the loop.
+  // stage t % NSTAGE is refilled with slab t+NSTAGE right after the barrier.  Every
+  // iteration of that loop issues the same number of loads, so the wait counts are
+  // constants and the body has no branch in it; the last NSTAGE slabs, which have nothing
+  // left to prefetch, run through a second copy of the body without loads that waits for
+  // everything outstanding.  A K tail (K % BK != 0) is multiplied after the loops.
   const int T_full = p.K / BK;
   constexpr int kLoadsPerSlab = Cfg::A_LOADS + Cfg::B_LOADS;
   constexpr int D = NSTAGE;                    // prefetch distance in slabs
@@ -396,7 +409,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // Own LDS reads retired (the stage may be refilled) and own loads of the wanted
   // slab landed, the loads of `kLater` later slabs may stay in flight; then all
   // waves meet.
-  auto hand_over = [&](auto later) {
+  auto hand_over = [&](auto later) __attribute__((always_inline)) {
     constexpr int kLater = decltype(later)::value;
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLater * kLoadsPerSlab) : "memory");
     __builtin_amdgcn_s_barrier();
@@ -409,15 +422,25 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     hand_over(std::integral_constant<int, D - 1>());
     read_frags(0, 0, 0);
     int stage = 0;
-    for (int t = 0; t < T_full; ++t) {
+    int t = 0;
+    for (; t < T_full - D; ++t) {              // slab t + D exists: refill the stage just freed
       const int next_stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
 #pragma unroll
       for (int kk = 0; kk < KK - 1; ++kk) step(kk & 1, true, stage, kk + 1, false, 0, 0);
       hand_over(std::integral_constant<int, D - 2>());
+      // (min: t + D <= T_full - 1 here; written out, it keeps the slab address in scalar registers)
       step((KK - 1) & 1, true, next_stage, 0, true, min(t + D, T_full - 1), stage);
       stage = next_stage;
     }
-    // the re-loads past the end and the last fragment reads are still in flight
+    for (; t < T_full; ++t) {                  // the last D slabs: nothing left to prefetch
+      const int next_stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+#pragma unroll
+      for (int kk = 0; kk < KK - 1; ++kk) step(kk & 1, true, stage, kk + 1, false, 0, 0);
+      hand_over(std::integral_constant<int, 0>());
+      step((KK - 1) & 1, true, next_stage, 0, false, 0, 0);
+      stage = next_stage;
+    }
+    // the last fragment reads (of a stage nobody multiplies) are still in flight
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   }
   if (T_full * BK < p.K) {                     // K tail, through registers with zero fill
@@ -462,9 +485,15 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // in row order, and the global stores cover whole 128-byte lines.
   const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
   const int act = p.act;
+  // The lane-dependent addresses of the epilogue are derived from an opaque copy of the lane
+  // id made here, so that none of them is computed ahead of the K loop and carried through
+  // it in registers the loop has no room for.
+  int elane = lane;
+  asm volatile("" : "+v"(elane));
+  const int er = elane & 31, eh = elane >> 5;
 
   // bias of the 4 columns j .. j+3 (zero past N)
-  auto bias4 = [&](int j, float (&bv)[4]) {
+  auto bias4 = [&](int j, float (&bv)[4]) __attribute__((always_inline)) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) bv[e] = 0.0f;
     if (!bias) return;
@@ -489,14 +518,17 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   unsigned char* wt = smem + wave * (Cfg::WTM * OROWB);
 
   // Each accumulator is read once: + bias, activation, rounding, and out (to LDS or
-  // to memory).  `actf` is a compile-time functor: one copy of the loops per activation.
-  auto drain = [&](auto actf) {
+  // to memory).  `actf` and `via_lds` are compile-time: one straight-line copy of the loops
+  // per activation and destination (a run-time test per accumulator group costs a taken
+  // branch each, which adds up to microseconds per tile).
+  auto drain = [&](auto actf, auto via_lds) __attribute__((always_inline)) {
+    constexpr bool kViaLds = decltype(via_lds)::value;
     const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C & 15) == 0) && (p.stride_c % 4 == 0);
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int j = col0 + wn * Cfg::WTN + n * 32 + g * 8 + fh * 4;
+        const int j = col0 + wn * Cfg::WTN + n * 32 + g * 8 + eh * 4;
         float bv[4];
         bias4(j, bv);
 #pragma unroll
@@ -504,16 +536,16 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][g * 4 + e] + bv[e]);
-          if (through_lds) {
+          if constexpr (kViaLds) {
             // chunk q of row r sits at chunk slot q ^ ((r >> 1) & 7): spreads the 32 rows
             // a write instruction touches over the banks
-            const int r = m * 32 + fr, q = n * 4 + g;
+            const int r = m * 32 + er, q = n * 4 + g;
             u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
-            *(u32x2_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & 7)) * 16) + fh * 8) = w;
+            *(u32x2_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & 7)) * 16) + eh * 8) = w;
           } else {
             // fp32 output, or C rows that are not 16-byte aligned: store from the
             // accumulator layout
-            const int i = row0 + wm * Cfg::WTM + m * 32 + fr;
+            const int i = row0 + wm * Cfg::WTM + m * 32 + er;
             if (i >= p.M || j >= p.N) continue;
             const bool full = (j + 3 < p.N);
             const int64_t o = batch * p.stride_c + (int64_t)i * p.ldc + j;
@@ -543,25 +575,29 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       }
     }
   };
+  auto drain_by_activation = [&](auto via_lds) __attribute__((always_inline)) {
+    switch (act) {
+      case kActRelu: drain([](float t) { return fmaxf(t, 0.0f); }, via_lds); break;
+      case kActGeluErf: drain([](float t) { return gelu_erf_f32(t); }, via_lds); break;
+      case kActGeluTanh: drain([](float t) { return gelu_tanh_f32(t); }, via_lds); break;
+      case kActSwishScale: { const float c = p.scale; drain([c](float t) { return swish_scale_f32(t, c); }, via_lds); } break;
+      case kActSigmoidScaleResidual: { const float c = p.scale; drain([c](float t) { return sigmoid_scale_residual_f32(t, c); }, via_lds); } break;
+      default: drain([](float t) { return t; }, via_lds); break;
+    }
+  };
 
-  if (through_lds) {
-    __builtin_amdgcn_s_barrier();              // all waves are done reading the slab stages
-    asm volatile("" ::: "memory");
+  if (!through_lds) {
+    drain_by_activation(std::false_type());
+    return;
   }
-  switch (act) {
-    case kActRelu: drain([](float t) { return fmaxf(t, 0.0f); }); break;
-    case kActGeluErf: drain([](float t) { return gelu_erf_f32(t); }); break;
-    case kActGeluTanh: drain([](float t) { return gelu_tanh_f32(t); }); break;
-    case kActSwishScale: { const float c = p.scale; drain([c](float t) { return swish_scale_f32(t, c); }); } break;
-    case kActSigmoidScaleResidual: { const float c = p.scale; drain([c](float t) { return sigmoid_scale_residual_f32(t, c); }); } break;
-    default: drain([](float t) { return t; }); break;
-  }
-  if (!through_lds) return;
+  __builtin_amdgcn_s_barrier();                // all waves are done reading the slab stages
+  asm volatile("" ::: "memory");
+  drain_by_activation(std::true_type());
 
   TO* Cb = (TO*)p.C + batch * p.stride_c;
 #pragma unroll
   for (int it = 0; it < Cfg::WTM / RPI2; ++it) {
-    const int r = it * RPI2 + lane / CH, q = lane % CH;
+    const int r = it * RPI2 + elane / CH, q = elane % CH;
     const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & 7)) * 16));
     const int i = row0 + wm * Cfg::WTM + r;
     const int j = col0 + wn * Cfg::WTN + q * 8;

@@ -77,8 +77,10 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
   constexpr int P = kSkinnyPieces;
   constexpr int DEPTH = 2;                       // rows a wave keeps requested (more gains nothing)
   // One or two x rows live in registers (each lane keeps the pieces it multiplies
-  // with); more rows are staged in LDS and re-read for every row of W.
-  constexpr bool kXInRegs = MB <= 2;
+  // with); more rows are staged in LDS and re-read for every row of W.  Two rows of x plus
+  // the two rows of W in flight are 256 registers: too many at two waves per SIMD, where a
+  // wave has 256 in all.
+  constexpr bool kXInRegs = MB == 1 || (MB == 2 && WAVES <= 4);
   __shared__ __attribute__((aligned(16))) unsigned char xs[kXInRegs ? 16 : MB * kSkinnyKC * 2];
   u32x4_t xr[kXInRegs ? MB : 1][P];
 

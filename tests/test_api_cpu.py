@@ -243,3 +243,25 @@ def test_config_table(g):
     d16 = g.GemmDesc(32, 4096, 4096)
     with pytest.raises(g.GemmError):                                # skinny kernels stop at M = 16
         g.gemm_create_config(d16, names.index("skinnymfma_r1_u8"))
+
+
+def test_build_guard_flags_kernels_that_use_scratch_memory():
+    """The build refuses a library in which a kernel keeps data in scratch memory or spills vector
+    registers (scalar registers parked in vector-register lanes are fine)."""
+    from paper_2603_12440_amd.build import kernels_with_scratch
+    remarks = "\n".join([
+        "a.hpp:1:1: remark: Function Name: kernel_ok [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     VGPRs: 128 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     SGPRs Spill: 19 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark: Function Name: kernel_stack [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     ScratchSize [bytes/lane]: 1408 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark: Function Name: kernel_spill [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     ScratchSize [bytes/lane]: 60 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hpp:1:1: remark:     VGPRs Spill: 50 [-Rpass-analysis=kernel-resource-usage]",
+        "warning: something else",
+    ])
+    assert kernels_with_scratch(remarks) == ["kernel_stack", "kernel_spill"]
+    assert kernels_with_scratch("") == []
