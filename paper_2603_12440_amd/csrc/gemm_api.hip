@@ -243,6 +243,7 @@ const Config kConfigs[] = {
     MFMA_CFG(256, 128, 64, 2, 2, 2),
     MFMA_CFG(128, 128, 64, 2, 2, 2),
     MFMA_CFG(256, 256, 64, 4, 4, 2),
+    MFMA_CFG(256, 192, 64, 4, 2, 2),
     MFMA8_CFG(256, 256, 128, 2, 4, 2),
     MFMA8_CFG(128, 128, 128, 2, 2, 2),
     SKINNY_CFG(1, 4, 1),
@@ -365,7 +366,8 @@ int find_config(const char* name) {
 double mfma_cost(const Config& c, int64_t M, int64_t N, int64_t K, int64_t batch) {
   const int area = c.bm * c.bn;
   const int per_cu = area <= 128 * 128 ? 2 : 1;                 // workgroups that fit one CU's LDS
-  const double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 128 ? 0.75 : 0.84);
+  // (256x192 measured: 0.85 - 1.03 of the 256x256 tile per FLOP on 4096x6144x4096, 4096x14336x4096, 8192^3)
+  const double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 192 ? 0.88 : (area >= 256 * 128 ? 0.75 : 0.84));
   const double tiles = (double)((M + c.bm - 1) / c.bm) * (double)((N + c.bn - 1) / c.bn) * (double)batch;
   const double rounds = (double)(int64_t)((tiles + kNumCUs * per_cu - 1) / (kNumCUs * per_cu));
   // workgroups that actually share a CU (a lone workgroup runs about per_cu times faster)
@@ -406,7 +408,8 @@ int64_t split_columns(const gemm_desc_t& d, int big, double single_cost) {
   if (best_mfma(rest, &rest_cost) < 0) return 0;
   const double launch = 3.0 * 2.7e6;
   const double split_cost = mfma_cost(c, d.M, n_first, d.K, 1) + rest_cost + launch;
-  return split_cost < 0.97 * single_cost ? n_first : 0;
+  // (a margin of a tenth: where the model saw 3 - 7 %, the second launch measured no gain)
+  return split_cost < 0.90 * single_cost ? n_first : 0;
 }
 
 // Built-in choice.  MFMA tile: cheapest under a small cost model (wave quantisation over

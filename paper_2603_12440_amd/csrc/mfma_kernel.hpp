@@ -485,11 +485,16 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // in row order, and the global stores cover whole 128-byte lines.
   const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
   const int act = p.act;
-  // The lane-dependent addresses of the epilogue are derived from an opaque copy of the lane
-  // id made here, so that none of them is computed ahead of the K loop and carried through
-  // it in registers the loop has no room for.
-  int elane = lane;
-  asm volatile("" : "+v"(elane));
+  // The lane-dependent addresses of the epilogue are derived from a lane id that is computed
+  // afresh where it is needed (from an opaque zero, so that the compiler can neither hoist it
+  // above the K loop nor keep one copy alive across the accumulator reads): the K loop and
+  // the drain have no register to spare for them.  (All 64 lanes are active here.)
+  auto fresh_lane = []() __attribute__((always_inline)) {
+    unsigned z = 0;
+    asm volatile("" : "+v"(z));
+    return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, z));
+  };
+  const int elane = fresh_lane();
   const int er = elane & 31, eh = elane >> 5;
 
   // bias of the 4 columns j .. j+3 (zero past N)
@@ -511,10 +516,11 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   const bool through_lds = !p.c_f32 && (p.ldc % 8 == 0) && (p.stride_c % 8 == 0) &&
                            (((uintptr_t)p.C & 15) == 0);
   constexpr int OROWB = Cfg::WTN * 2;           // bytes per row of the wave's block
-  constexpr int CH = OROWB / 16;                // 16-byte chunks per row
-  constexpr int RPI2 = 64 / CH;                // rows one wave-wide 16-byte access covers
+  constexpr int CH = OROWB / 16;                // 16-byte chunks per row (8, 12 or 16)
+  constexpr int OSW = CH % 8 == 0 ? 7 : 3;      // chunk-slot swizzle mask: stays inside the row for CH = 12
   static_assert(Cfg::LDS_BYTES >= BM * BN * 2, "the output block must fit the slab stages");
-  static_assert(CH >= 8 && 64 % CH == 0, "row of the wave block: at least 128 bytes");
+  static_assert(CH >= 8 && CH % 4 == 0 && (Cfg::WTM * CH) % 64 == 0,
+                "row of the wave block: at least 128 bytes, and the block a whole number of wave-wide accesses");
   unsigned char* wt = smem + wave * (Cfg::WTM * OROWB);
 
   // Each accumulator is read once: + bias, activation, rounding, and out (to LDS or
@@ -537,11 +543,11 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][g * 4 + e] + bv[e]);
           if constexpr (kViaLds) {
-            // chunk q of row r sits at chunk slot q ^ ((r >> 1) & 7): spreads the 32 rows
+            // chunk q of row r sits at chunk slot q ^ ((r >> 1) & OSW): spreads the 32 rows
             // a write instruction touches over the banks
             const int r = m * 32 + er, q = n * 4 + g;
             u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
-            *(u32x2_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & 7)) * 16) + eh * 8) = w;
+            *(u32x2_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & OSW)) * 16) + eh * 8) = w;
           } else {
             // fp32 output, or C rows that are not 16-byte aligned: store from the
             // accumulator layout
@@ -595,10 +601,13 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   drain_by_activation(std::true_type());
 
   TO* Cb = (TO*)p.C + batch * p.stride_c;
+  const int slane = fresh_lane();
 #pragma unroll
-  for (int it = 0; it < Cfg::WTM / RPI2; ++it) {
-    const int r = it * RPI2 + elane / CH, q = elane % CH;
-    const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & 7)) * 16));
+  for (int it = 0; it < Cfg::WTM * CH / 64; ++it) {
+    // the block's 16-byte chunks in row-major order, 64 per access: whole rows (or runs of rows)
+    const int e = it * 64 + slane;
+    const int r = e / CH, q = e % CH;
+    const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & OSW)) * 16));
     const int i = row0 + wm * Cfg::WTM + r;
     const int j = col0 + wn * Cfg::WTN + q * 8;
     if (i < p.M && j < p.N) {

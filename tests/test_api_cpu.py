@@ -205,6 +205,13 @@ def test_kernel_choice(g):
         return info
     assert "kernel=mfma_256x256" in kernel(M=8192, N=8192, K=8192)
     assert "grid=1024,1,1" in kernel(M=8192, N=8192, K=8192)
+    # wave quantisation: 384 tiles of 256x256 are 1.5 rounds of the 256 CUs, 512 tiles of 256x192 two full ones
+    assert "kernel=mfma_256x192x64_w4x2_s2" in kernel(M=4096, N=6144, K=4096)
+    assert "grid=512,1,1" in kernel(M=4096, N=6144, K=4096)
+    assert "kernel=mfma_256x256" in kernel(M=4096, N=4096, K=14336)
+    # one round and an eighth: the whole round on the big tile, the rest as a second launch
+    two = kernel(M=4096, N=4608, K=4096)
+    assert "kernel=mfma_256x256" in two and "columns=0..4095" in two and "columns=4096.." in two
     for m in (1, 4):
         assert "kernel=skinny_m" in kernel(M=m, N=8192, K=8192)
     assert "kernel=skinny_m1_w8_g1" in kernel(M=1, N=8192, K=8192)

@@ -397,7 +397,7 @@ def test_split_plan_two_launches(g, oracle):
     """Shapes whose 256x256 tiles do not fill whole rounds of the CUs are planned as two
     launches (big tiles for the full rounds, another shape for the remaining columns): the
     seam must be invisible.  Integer data: bit exact; bias + ReLU across the seam."""
-    w = wl.Workload("t", 4096, 6144, 1024, epilogue="bias_relu", seed_a=3, seed_b=4, seed_bias=5)
+    w = wl.Workload("t", 4096, 4608, 1024, epilogue="bias_relu", seed_a=3, seed_b=4, seed_bias=5)
     sa, sb = wl.operand_shapes(w)
     A = wl.small_integers(sa, 3, -1, 1)
     B = wl.small_integers(sb, 4, -1, 1)
