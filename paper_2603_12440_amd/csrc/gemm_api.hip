@@ -246,6 +246,7 @@ const Config kConfigs[] = {
     MFMA_CFG(256, 192, 64, 4, 2, 2),
     MFMA8_CFG(256, 256, 128, 2, 4, 2),
     MFMA8_CFG(128, 128, 128, 2, 2, 2),
+    MFMA8_CFG(256, 192, 128, 4, 2, 2),
     SKINNY_CFG(1, 4, 1),
     SKINNY_CFG(2, 4, 1),
     SKINNY_CFG(4, 4, 1),

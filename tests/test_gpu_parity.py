@@ -493,7 +493,7 @@ def test_splitk_full_size_against_plain_plan_and_oracle_samples(g, oracle):
 
 # ---- fp8 (E4M3) operands ----------------------------------------------------------------------
 
-F8_CONFIGS = ["mfma8_256x256x128_w2x4_s2", "mfma8_128x128x128_w2x2_s2"]
+F8_CONFIGS = ["mfma8_256x256x128_w2x4_s2", "mfma8_128x128x128_w2x2_s2", "mfma8_256x192x128_w4x2_s2"]
 
 
 def test_f8_exact_integers_ragged_shapes_and_k_tails(g, oracle):
