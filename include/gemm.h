@@ -139,8 +139,9 @@ const char* gemm_config_name(int config);      /* NULL if out of range; static s
  * A, B, C, bias: device pointers laid out as the plan's descriptor says, owned
  * by the caller; A, B and bias are only read, C is only written and must not
  * overlap A or B.  bias must be non-NULL exactly when the epilogue has a bias.
- * Every call recomputes everything; nothing is cached between calls.  A plan is
- * immutable: it may be shared by threads and streams.
+ * Every call recomputes everything; no result is cached between calls.  A plan
+ * may be shared by threads and streams.  (In tuning mode, see gemm_set_autotune, the
+ * first call for a problem also times the alternatives.)
  */
 int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C,
              const void* bias, void* hip_stream);
@@ -161,6 +162,27 @@ int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C,
  */
 int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, const void* bias,
               void* hip_stream, double min_seconds, int* best_config, float* us_per_config);
+
+/*
+ * Tuning mode - the paper's parameter optimisation over templated kernels (Sec. 3.4) as a
+ * switch.  Off by default; on when the environment variable GEMM_TUNE is set to anything but
+ * "" or "0" at the library's first use, or after gemm_set_autotune(1).  While it is on, the
+ * first gemm_run of a plan from gemm_create (or gemm_create_config(-1)) times every
+ * applicable instantiation (as gemm_tune does, 0.02 s each) and the plan as built on the
+ * caller's own buffers, keeps the fastest for that plan, and remembers it per problem (sizes,
+ * layouts, dtypes, epilogue, leading dimensions, batch strides) for the rest of the process:
+ * later plans of the same problem skip the timing.  That first call blocks (it synchronises
+ * the stream, so it must not be made under stream capture), overwrites C several times with
+ * the correct result, and needs A, B and C 16-byte aligned (otherwise the plan runs untuned).
+ * Plans of gemm_create_config(config >= 0) and gemm_create_splitk are never re-planned.  The
+ * table lives in host memory; no device memory is allocated.  Thread-safe.
+ *   gemm_set_autotune      switch the mode (non-zero = on); returns the previous setting (0 / 1)
+ *   gemm_autotune_entries  number of problems remembered
+ *   gemm_autotune_clear    forget them (plans already timed keep their choice)
+ */
+int gemm_set_autotune(int enabled);
+int gemm_autotune_entries(void);
+int gemm_autotune_clear(void);
 
 /*
  * Split-K: for products with few output tiles and a long K (too few tiles to occupy the 256

@@ -114,6 +114,12 @@ def load_library():
                               ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
     lib.gemm_destroy.restype = ctypes.c_int
     lib.gemm_destroy.argtypes = [ctypes.c_void_p]
+    lib.gemm_set_autotune.restype = ctypes.c_int
+    lib.gemm_set_autotune.argtypes = [ctypes.c_int]
+    lib.gemm_autotune_entries.restype = ctypes.c_int
+    lib.gemm_autotune_entries.argtypes = []
+    lib.gemm_autotune_clear.restype = ctypes.c_int
+    lib.gemm_autotune_clear.argtypes = []
     lib.gemm_status_string.restype = ctypes.c_char_p
     lib.gemm_status_string.argtypes = [ctypes.c_int]
     lib.gemm_plan_info.restype = ctypes.c_int
@@ -240,6 +246,19 @@ def gemm_tune(desc: GemmDesc, A, B, C, bias=None, stream: Optional[int] = None,
     _check(lib.gemm_tune(ctypes.byref(desc), _dev_ptr(A), _dev_ptr(B), _dev_ptr(C), _dev_ptr(bias),
                          stream or None, float(min_seconds), ctypes.byref(best), us))
     return best.value, {gemm_config_name(i): float(us[i]) for i in range(n) if us[i] >= 0}
+
+
+def gemm_set_autotune(enabled: bool) -> bool:
+    """Switches tuning mode (include/gemm.h); returns the previous setting."""
+    return bool(load_library().gemm_set_autotune(1 if enabled else 0))
+
+
+def gemm_autotune_entries() -> int:
+    return int(load_library().gemm_autotune_entries())
+
+
+def gemm_autotune_clear() -> None:
+    _check(load_library().gemm_autotune_clear())
 
 
 def gemm_destroy(plan: Optional[Plan]) -> None:

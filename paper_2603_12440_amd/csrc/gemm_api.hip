@@ -9,9 +9,13 @@
 
 #include <atomic>
 #include <cstdio>
+#include <cstdlib>
 #include <cmath>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "../../include/gemm.h"
 #include "common.hpp"
@@ -47,6 +51,15 @@ struct gemm_plan {
   // the fp32 workspace (cfg, grid, ... above are then those of the inner plan, for reporting).
   int splits;
   gemm_plan* inner;
+  // Tuning mode (gemm_set_autotune / GEMM_TUNE=1): `d_user` is the caller's resolved problem
+  // (d may have been narrowed to the first launch's columns), `built_in` says the kernel was
+  // the library's choice, and once the problem has been timed `tune_state` is 1 (this plan
+  // is the fastest) or 2 (`tuned`, a plan of the fastest configuration, runs instead).
+  // Both are set once, with atomic operations; a plan stays shareable between threads.
+  gemm_desc_t d_user;
+  int built_in;
+  int tune_state;
+  gemm_plan* tuned;
 };
 
 namespace {
@@ -515,6 +528,10 @@ static int create_resolved(const gemm_desc_t& d, int config, bool allow_two_laun
   pl->tail_off_b = pl->tail_off_c = pl->tail_off_bias = 0;
   pl->splits = 0;
   pl->inner = nullptr;
+  pl->d_user = d;
+  pl->built_in = auto_choice && allow_two_launches;   // (second launches and split-K inner plans are parts, not plans)
+  pl->tune_state = 0;
+  pl->tuned = nullptr;
   if (auto_choice && allow_two_launches && kConfigs[config].kind == KIND_MFMA) {
     double single_cost = 0;
     best_mfma(d, &single_cost);
@@ -615,6 +632,8 @@ int gemm_create_splitk(const gemm_desc_t* desc, int splits, gemm_plan_t** out_pl
   gemm_plan* pl = new (std::nothrow) gemm_plan(*inner);
   if (!pl) { gemm_destroy(inner); return GEMM_ERR_NULL; }
   pl->d = d;
+  pl->d_user = d;
+  pl->built_in = 0;
   pl->splits = splits;
   pl->inner = inner;
   *out_plan = pl;
@@ -663,8 +682,9 @@ int gemm_create(const gemm_desc_t* desc, gemm_plan_t** out_plan) {
   return gemm_create_config(desc, -1, out_plan);
 }
 
-int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, const void* bias,
-             void* hip_stream) {
+// The launches of one plan, arguments checked; no tuning logic.
+static int run_plan(const gemm_plan_t* plan, const void* A, const void* B, void* C, const void* bias,
+                    void* hip_stream) {
   if (!plan || !A || !B || !C) return GEMM_ERR_NULL;
   if (plan->inner) return GEMM_ERR_WORKSPACE;
   const gemm_desc_t& d = plan->d;
@@ -690,6 +710,47 @@ int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, con
   return GEMM_OK;
 }
 
+// Mean microseconds per launch of one plan under the paper's timing protocol (App.
+// "Benchmarking kernel runtime"): a few initial trials size the loops, a warm-up of at least
+// min_seconds and 10 launches, then inner loops of >= min(0.01 s, min_seconds) between two
+// event synchronisations until at least min_seconds and 10 launches have been measured.
+static int time_plan(const gemm_plan_t* pl, const void* A, const void* B, void* C, const void* bias,
+                     void* hip_stream, hipEvent_t e0, hipEvent_t e1, double min_seconds, double* us) {
+  hipStream_t stream = (hipStream_t)hip_stream;
+  int status = GEMM_OK;
+  // n launches between two events; returns elapsed seconds (< 0 on failure)
+  auto timed = [&](long n) -> double {
+    if (hipEventRecord(e0, stream) != hipSuccess) return -1.0;
+    for (long i = 0; i < n; ++i) {
+      int r = run_plan(pl, A, B, C, bias, hip_stream);
+      if (r != GEMM_OK) { status = r; return -1.0; }
+    }
+    if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0;
+    return (double)ms * 1e-3;
+  };
+  auto failed = [&]() { return status != GEMM_OK ? status : GEMM_ERR_LAUNCH; };
+  const double inner_s = min_seconds < 0.01 ? min_seconds : 0.01;
+  double t = timed(3);                                   // initial trials: rough runtime
+  if (t < 0) return failed();
+  const double per = t / 3 > 1e-7 ? t / 3 : 1e-7;
+  const long inner = (long)(inner_s / per) + 1;
+  long warm = (long)(min_seconds / per) + 1;             // warm-up: at least min_seconds and 10 launches
+  if (warm < 10) warm = 10;
+  if (timed(warm) < 0) return failed();
+  double total = 0.0;
+  long launches = 0;
+  while (total < min_seconds || launches < 10) {
+    const double dt = timed(inner);
+    if (dt < 0) return failed();
+    total += dt;
+    launches += inner;
+  }
+  *us = total / (double)launches * 1e6;
+  return GEMM_OK;
+}
+
 int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, const void* bias,
               void* hip_stream, double min_seconds, int* best_config, float* us_per_config) {
   if (!desc || !A || !B || !C || !best_config) return GEMM_ERR_NULL;
@@ -698,54 +759,20 @@ int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, co
   int rc = resolve(desc, &d);
   if (rc != GEMM_OK) return rc;
   if (!(min_seconds >= 0.0)) min_seconds = 0.0;
-  hipStream_t stream = (hipStream_t)hip_stream;
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_LAUNCH; }
   if (hipEventCreate(&e1) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(e0); return GEMM_ERR_LAUNCH; }
-  const double inner_s = min_seconds < 0.01 ? min_seconds : 0.01;
   double best_us = 0.0;
   int status = GEMM_OK;
-
-  // n launches between two events; returns elapsed seconds (< 0 on failure)
-  auto timed = [&](const gemm_plan* pl, long n) -> double {
-    if (hipEventRecord(e0, stream) != hipSuccess) return -1.0;
-    for (long i = 0; i < n; ++i) {
-      int r = gemm_run(pl, A, B, C, bias, hip_stream);
-      if (r != GEMM_OK) { status = r; return -1.0; }
-    }
-    if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0;
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0;
-    return (double)ms * 1e-3;
-  };
-
   for (int i = 0; i < kNumConfigs && status == GEMM_OK; ++i) {
     if (us_per_config) us_per_config[i] = -1.0f;
     if (!applicable(kConfigs[i], d)) continue;
     gemm_plan_t* pl = nullptr;
-    if (gemm_create_config(desc, i, &pl) != GEMM_OK) continue;
-    // initial trials: rough runtime
-    double t = timed(pl, 3);
-    if (t < 0) { gemm_destroy(pl); if (status == GEMM_OK) status = GEMM_ERR_LAUNCH; break; }
-    double per = t / 3 > 1e-7 ? t / 3 : 1e-7;
-    long inner = (long)(inner_s / per) + 1;
-    // warm-up: at least min_seconds and 10 launches
-    long warm = (long)(min_seconds / per) + 1;
-    if (warm < 10) warm = 10;
-    if (timed(pl, warm) < 0) { gemm_destroy(pl); if (status == GEMM_OK) status = GEMM_ERR_LAUNCH; break; }
-    // measurement: inner loops until at least min_seconds and 10 launches
-    double total = 0.0;
-    long launches = 0;
-    bool failed = false;
-    while (total < min_seconds || launches < 10) {
-      double dt = timed(pl, inner);
-      if (dt < 0) { failed = true; break; }
-      total += dt;
-      launches += inner;
-    }
+    if (create_resolved(d, i, true, &pl) != GEMM_OK) continue;
+    double us = 0.0;
+    status = time_plan(pl, A, B, C, bias, hip_stream, e0, e1, min_seconds, &us);
     gemm_destroy(pl);
-    if (failed) { if (status == GEMM_OK) status = GEMM_ERR_LAUNCH; break; }
-    const double us = total / (double)launches * 1e6;
+    if (status != GEMM_OK) break;
     if (us_per_config) us_per_config[i] = (float)us;
     if (*best_config < 0 || us < best_us) { *best_config = i; best_us = us; }
   }
@@ -755,12 +782,128 @@ int gemm_tune(const gemm_desc_t* desc, const void* A, const void* B, void* C, co
   return *best_config >= 0 ? GEMM_OK : GEMM_ERR_UNSUPPORTED;
 }
 
+// ---- tuning mode --------------------------------------------------------------------------
+// The paper's parameter optimisation (Sec. 3.4) as a switch: with it on, the first gemm_run of
+// a problem times every applicable instantiation and the built-in plan on the caller's own
+// buffers and remembers the winner per problem for the rest of the process.
+namespace {
+
+struct TuneKey {
+  int64_t v[17];
+  bool operator<(const TuneKey& o) const { return std::memcmp(v, o.v, sizeof(v)) < 0; }
+};
+TuneKey tune_key(const gemm_desc_t& d) {                 // everything but the epilogue's scalar
+  TuneKey k;
+  const int64_t f[17] = {d.M, d.N, d.K, d.batch, d.layout_a, d.layout_b, d.layout_c, d.dtype_a, d.dtype_b,
+                         d.dtype_c, d.epilogue, d.lda, d.ldb, d.ldc, d.stride_a, d.stride_b, d.stride_c};
+  std::memcpy(k.v, f, sizeof(f));
+  return k;
+}
+std::mutex g_tune_mutex;
+std::map<TuneKey, int> g_tune_cache;                     // problem -> fastest configuration, -1 = the built-in plan
+std::atomic<int> g_autotune{-1};                         // -1: not yet read from the environment
+constexpr double kAutotuneSeconds = 0.02;                // per configuration: warm-up and measurement each
+
+bool autotune_on() {
+  int v = g_autotune.load();
+  if (v < 0) {
+    const char* e = std::getenv("GEMM_TUNE");
+    int from_env = (e && e[0] && std::strcmp(e, "0") != 0) ? 1 : 0;
+    int expected = -1;
+    g_autotune.compare_exchange_strong(expected, from_env);
+    v = g_autotune.load();
+  }
+  return v == 1;
+}
+
+// Decide how `plan` runs from now on (tune_state 1: as it is; 2: through plan->tuned).
+int autotune_plan(const gemm_plan_t* plan, const void* A, const void* B, void* C, const void* bias,
+                  void* hip_stream) {
+  gemm_plan_t* self = const_cast<gemm_plan_t*>(plan);    // only the two set-once tuning fields are written
+  const gemm_desc_t& d = plan->d_user;
+  std::lock_guard<std::mutex> lock(g_tune_mutex);         // one tuning run at a time; later callers find the entry
+  if (__atomic_load_n(&self->tune_state, __ATOMIC_ACQUIRE) != 0) return GEMM_OK;
+  int cfg = -1;
+  const TuneKey key = tune_key(d);
+  auto it = g_tune_cache.find(key);
+  if (it != g_tune_cache.end()) {
+    cfg = it->second;
+  } else {
+    int best = -1;
+    std::vector<float> us(kNumConfigs, -1.0f);
+    int rc = gemm_tune(&d, A, B, C, bias, hip_stream, kAutotuneSeconds, &best, us.data());
+    if (rc != GEMM_OK) return rc;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_LAUNCH; }
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(e0); return GEMM_ERR_LAUNCH; }
+    double own = 0.0;
+    rc = time_plan(plan, A, B, C, bias, hip_stream, e0, e1, kAutotuneSeconds, &own);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != GEMM_OK) { (void)hipGetLastError(); return rc; }
+    // a configuration replaces the built-in plan only for a clear win
+    const bool same = best == plan->cfg_index && !plan->tail;
+    cfg = (!same && (double)us[best] < 0.98 * own) ? best : -1;
+    g_tune_cache[key] = cfg;
+  }
+  if (cfg >= 0 && !(cfg == plan->cfg_index && !plan->tail)) {
+    gemm_plan_t* tp = nullptr;
+    const int rc = create_resolved(d, cfg, true, &tp);
+    if (rc != GEMM_OK) return rc;
+    tp->built_in = 0;
+    self->tuned = tp;
+    __atomic_store_n(&self->tune_state, 2, __ATOMIC_RELEASE);
+  } else {
+    __atomic_store_n(&self->tune_state, 1, __ATOMIC_RELEASE);
+  }
+  return GEMM_OK;
+}
+
+}  // namespace
+
+int gemm_set_autotune(int enabled) {
+  const int before = autotune_on() ? 1 : 0;
+  g_autotune.store(enabled ? 1 : 0);
+  return before;
+}
+
+int gemm_autotune_entries(void) {
+  std::lock_guard<std::mutex> lock(g_tune_mutex);
+  return (int)g_tune_cache.size();
+}
+
+int gemm_autotune_clear(void) {
+  std::lock_guard<std::mutex> lock(g_tune_mutex);
+  g_tune_cache.clear();
+  return GEMM_OK;
+}
+
+int gemm_run(const gemm_plan_t* plan, const void* A, const void* B, void* C, const void* bias,
+             void* hip_stream) {
+  if (plan && plan->built_in && !plan->inner && autotune_on()) {
+    int state = __atomic_load_n(&plan->tune_state, __ATOMIC_ACQUIRE);
+    if (state == 0) {
+      // arguments are checked before anything is timed with them
+      if (!A || !B || !C) return GEMM_ERR_NULL;
+      if (epilogue_has_bias(plan->d.epilogue) != (bias != nullptr)) return GEMM_ERR_NULL;
+      if (((uintptr_t)A & 15) || ((uintptr_t)B & 15) || ((uintptr_t)C & 15) || ((uintptr_t)bias & 3))
+        return run_plan(plan, A, B, C, bias, hip_stream);   // (unusual alignment: no tuning, the plan's own checks decide)
+      const int rc = autotune_plan(plan, A, B, C, bias, hip_stream);
+      if (rc != GEMM_OK) return rc;
+      state = __atomic_load_n(&plan->tune_state, __ATOMIC_ACQUIRE);
+    }
+    if (state == 2) return run_plan(plan->tuned, A, B, C, bias, hip_stream);
+  }
+  return run_plan(plan, A, B, C, bias, hip_stream);
+}
+
 int gemm_destroy(gemm_plan_t* plan) {
   if (plan) {
     if (plan->inner) {                 // a split-K plan is a copy of its inner plan's launch data
       gemm_destroy(plan->inner);
     } else {
       delete plan->tail;
+      if (plan->built_in && plan->tuned) gemm_destroy(plan->tuned);
     }
   }
   delete plan;
@@ -787,6 +930,14 @@ const char* gemm_status_string(int status) {
 
 int gemm_plan_info(const gemm_plan_t* plan, char* buf, size_t n) {
   if (!plan || (!buf && n)) return GEMM_ERR_NULL;
+  if (plan->built_in && __atomic_load_n(&plan->tune_state, __ATOMIC_ACQUIRE) == 2) {
+    // timed in tuning mode and replaced: report what runs
+    const int len = gemm_plan_info(plan->tuned, buf, n);
+    if (len < 0) return len;
+    const char* tag = " (tuned)";
+    if (buf && (size_t)len < n) std::snprintf(buf + len, n - (size_t)len, "%s", tag);
+    return len + (int)std::strlen(tag);
+  }
   const Config& c = *plan->cfg;
   if (plan->inner) {
     return std::snprintf(buf, n, "kernel=splitk_%d+%s tile=%dx%dx%d grid=%u,%u,%u block=%u lds=%d workspace=%zu",

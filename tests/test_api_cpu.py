@@ -25,7 +25,8 @@ def test_every_declared_symbol_is_exported(g):
     names = set(re.findall(r"\b(gemm_[a-z_]+)\s*\(", header))
     assert {"gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
             "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune",
-            "gemm_create_splitk", "gemm_workspace_bytes", "gemm_run_workspace"} <= names
+            "gemm_create_splitk", "gemm_workspace_bytes", "gemm_run_workspace",
+            "gemm_set_autotune", "gemm_autotune_entries", "gemm_autotune_clear"} <= names
     rope = open(os.path.join(ROOT, "include", "rope.h")).read()
     rope = re.sub(r"/\*.*?\*/", "", rope, flags=re.S)
     rope_names = set(re.findall(r"\b(rope_[a-z_]+)\s*\(", rope))
@@ -42,7 +43,8 @@ def test_every_declared_symbol_is_exported(g):
 def test_binding_exposes_the_same_names(g):
     for n in ("gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string", "gemm_plan_info",
               "gemm_create_config", "gemm_config_count", "gemm_config_name", "gemm_tune",
-              "gemm_create_splitk", "gemm_workspace_bytes", "gemm_run_workspace", "rope_apply"):
+              "gemm_create_splitk", "gemm_workspace_bytes", "gemm_run_workspace", "rope_apply",
+              "gemm_set_autotune", "gemm_autotune_entries", "gemm_autotune_clear"):
         assert callable(getattr(g, n))
 
 
@@ -272,3 +274,26 @@ def test_build_guard_flags_kernels_that_use_scratch_memory():
     ])
     assert kernels_with_scratch(remarks) == ["kernel_stack", "kernel_spill"]
     assert kernels_with_scratch("") == []
+
+
+def test_tuning_mode_switch_and_environment(g):
+    """Tuning mode is off by default, follows GEMM_TUNE at first use, and the switch returns the
+    previous setting; the table of remembered problems starts empty (no device needed)."""
+    import subprocess, sys
+    code = ("import paper_2603_12440_amd as g; "
+            "print(int(g.gemm_set_autotune(True)), int(g.gemm_set_autotune(False)), int(g.gemm_set_autotune(False)), "
+            "g.gemm_autotune_entries())")
+    def run(env_value):
+        env = dict(os.environ)
+        env.pop("GEMM_TUNE", None)
+        if env_value is not None:
+            env["GEMM_TUNE"] = env_value
+        out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, env=env, capture_output=True, text=True)
+        assert out.returncode == 0, out.stderr
+        return out.stdout.split()
+    assert run(None) == ["0", "1", "0", "0"]
+    assert run("0") == ["0", "1", "0", "0"]
+    assert run("") == ["0", "1", "0", "0"]
+    assert run("1") == ["1", "1", "0", "0"]
+    g.gemm_autotune_clear()
+    assert g.gemm_autotune_entries() == 0

@@ -409,6 +409,58 @@ def test_split_plan_two_launches(g, oracle):
     assert np.array_equal(wl.to_float64(C), ref["y"])
 
 
+def test_tuning_mode_times_once_per_problem_and_keeps_results_exact(g, oracle):
+    """Tuning mode (the paper's parameter optimisation as a switch): the first run of a problem
+    times the alternatives on the caller's buffers and remembers the winner; results stay bit
+    exact on integer data before, during and after; plans with an explicit configuration and a
+    second plan of the same problem do no timing of their own."""
+    dev = torch.device("cuda:0")
+    from helpers import gpu_desc
+    w = wl.Workload("t", 300, 520, 264, epilogue="bias_relu", seed_a=3, seed_b=4, seed_bias=5)
+    sa, sb = wl.operand_shapes(w)
+    A = wl.small_integers(sa, 3, -1, 1).to(dev)
+    B = wl.small_integers(sb, 4, -1, 1).to(dev)
+    bias = wl.small_integers((w.N,), 5, -3, 3, "f32").to(dev)
+    ref = run_oracle(oracle, w, A.cpu(), B.cpu(), bias.cpu(), want=("y",))["y"]
+    def run(plan):
+        C = torch.full((1, w.M, w.N), -768.0, dtype=wl.TORCH_DTYPE[w.dtype], device=dev)
+        g.gemm_run(plan, A, B, C, bias)
+        torch.cuda.synchronize()
+        return wl.to_float64(C.cpu())
+    g.gemm_autotune_clear()
+    before = g.gemm_set_autotune(True)
+    try:
+        assert g.gemm_autotune_entries() == 0
+        fixed = g.gemm_create_config(gpu_desc(g, w), cfg_index(g, "mfma_128x128x64_w2x2_s2"))
+        assert np.array_equal(run(fixed), ref) and g.gemm_autotune_entries() == 0      # explicit configuration: untouched
+        p1 = g.gemm_create(gpu_desc(g, w))
+        say("before: " + p1.info())
+        assert np.array_equal(run(p1), ref)                                            # timed here
+        assert g.gemm_autotune_entries() == 1
+        say("after:  " + p1.info())
+        assert np.array_equal(run(p1), ref)
+        p2 = g.gemm_create(gpu_desc(g, w))                                             # same problem: table hit
+        assert np.array_equal(run(p2), ref) and g.gemm_autotune_entries() == 1
+        assert p2.info() == p1.info()
+        w2 = wl.Workload("t", 4, 520, 264, seed_a=3, seed_b=4)                         # another problem (skinny kernels)
+        A2 = wl.small_integers(wl.operand_shapes(w2)[0], 3, -1, 1).to(dev)
+        ref2 = run_oracle(oracle, w2, A2.cpu(), B.cpu(), None, want=("y",))["y"]
+        p3 = g.gemm_create(gpu_desc(g, w2))
+        C2 = torch.empty((1, w2.M, w2.N), dtype=wl.TORCH_DTYPE[w2.dtype], device=dev)
+        g.gemm_run(p3, A2, B, C2, None)
+        torch.cuda.synchronize()
+        assert np.array_equal(wl.to_float64(C2.cpu()), ref2) and g.gemm_autotune_entries() == 2
+        for p in (fixed, p1, p2, p3):
+            g.gemm_destroy(p)
+    finally:
+        g.gemm_set_autotune(before)
+        g.gemm_autotune_clear()
+    # off again: a new plan of the same problem runs as built
+    p4 = g.gemm_create(gpu_desc(g, w))
+    assert np.array_equal(run(p4), ref) and g.gemm_autotune_entries() == 0 and "(tuned)" not in p4.info()
+    g.gemm_destroy(p4)
+
+
 # ---- split-K ------------------------------------------------------------------------------------
 
 def run_splitk(g, w, A, B, bias, splits, out_dtype=None, layout_c="row", pad_c=0, ws_slack=0):
