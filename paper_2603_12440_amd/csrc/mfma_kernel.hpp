@@ -206,6 +206,15 @@ struct MfmaTile {
                                     "many MFMAs as reads (wave blocks of at least 2 x 2 MFMA tiles)");
 };
 
+// f(integral_constant<int, I>) for I = FROM .. TO-1, unrolled at compile time
+template <int FROM, int TO_, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (FROM < TO_) {
+    f(std::integral_constant<int, FROM>());
+    static_for<FROM + 1, TO_>(f);
+  }
+}
+
 // T: operand type; TO: the 16-bit output type (outputs may also be fp32: MfmaArgs::c_f32).
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
@@ -522,11 +531,65 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   static_assert(CH >= 8 && CH % 4 == 0 && (Cfg::WTM * CH) % 64 == 0,
                 "row of the wave block: at least 128 bytes, and the block a whole number of wave-wide accesses");
   unsigned char* wt = smem + wave * (Cfg::WTM * OROWB);
+  // fp32 output goes through the same LDS pieces in passes of MP 32-row tiles (a wave's share of
+  // the stages holds a quarter to a half of its block in fp32): 16-byte writes in accumulator
+  // order, 16-byte reads in row order, stores that cover whole lines.
+  const bool through_lds32 = p.c_f32 && (p.ldc % 4 == 0) && (p.stride_c % 4 == 0) && (((uintptr_t)p.C & 15) == 0);
+  constexpr int OROWB32 = Cfg::WTN * 4;         // bytes per fp32 row of the wave's block
+  constexpr int CH32 = OROWB32 / 16;            // 16-byte chunks per row (16, 24 or 32)
+  constexpr int OSW32 = CH32 % 16 == 0 ? 15 : 7;
+  constexpr int kShare = Cfg::LDS_BYTES / Cfg::kWaves;           // bytes of LDS per wave
+  constexpr int MP = (kShare / (32 * OROWB32)) >= MT ? MT : (kShare / (32 * OROWB32) >= 2 ? 2 : 1);
+  static_assert(32 * OROWB32 <= kShare && MT % MP == 0 && (32 * MP * CH32) % 64 == 0,
+                "one 32-row tile of the wave block in fp32 must fit the wave's share of LDS");
+  unsigned char* wt32 = smem + wave * kShare;
 
   // Each accumulator is read once: + bias, activation, rounding, and out (to LDS or
   // to memory).  `actf` and `via_lds` are compile-time: one straight-line copy of the loops
   // per activation and destination (a run-time test per accumulator group costs a taken
   // branch each, which adds up to microseconds per tile).
+  // fp32 through LDS: m-tiles [MP pass, MP pass + MP) of every column tile, then their rows out
+  auto drain32 = [&](auto actf, auto pass_c) __attribute__((always_inline)) {
+    constexpr int pass = decltype(pass_c)::value;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int j = col0 + wn * Cfg::WTN + n * 32 + g * 8 + eh * 4;
+        float bv[4];
+        bias4(j, bv);
+#pragma unroll
+        for (int mm = 0; mm < MP; ++mm) {
+          const int m = pass * MP + mm;
+          f32x4_t w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = actf(acc[m][n][g * 4 + e] + bv[e]);
+          const int r = mm * 32 + er, q = n * 8 + g * 2 + eh;
+          *(f32x4_t*)(wt32 + r * OROWB32 + ((q ^ (r & OSW32)) * 16)) = w;
+        }
+      }
+    }
+    float* Cf = (float*)p.C + batch * p.stride_c;
+    const int slane32 = fresh_lane();
+#pragma unroll
+    for (int it = 0; it < 32 * MP * CH32 / 64; ++it) {
+      const int e = it * 64 + slane32;
+      const int r = e / CH32, q = e % CH32;
+      const f32x4_t val = *(const f32x4_t*)(wt32 + r * OROWB32 + ((q ^ (r & OSW32)) * 16));
+      const int i = row0 + wm * Cfg::WTM + pass * (32 * MP) + r;
+      const int j = col0 + wn * Cfg::WTN + q * 4;
+      if (i < p.M && j < p.N) {
+        float* c = Cf + (int64_t)i * p.ldc + j;
+        if (j + 4 <= p.N) {
+          __builtin_nontemporal_store(val, (f32x4_t*)c);
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            if (j + t < p.N) c[t] = val[t];
+        }
+      }
+    }
+  };
   auto drain = [&](auto actf, auto via_lds) __attribute__((always_inline)) {
     constexpr bool kViaLds = decltype(via_lds)::value;
     const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C & 15) == 0) && (p.stride_c % 4 == 0);
@@ -581,24 +644,37 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       }
     }
   };
-  auto drain_by_activation = [&](auto via_lds) __attribute__((always_inline)) {
+  // dest: 0 = memory from the accumulator layout, 1 = 16-bit through LDS, 2 = fp32 through LDS
+  auto drain_to = [&](auto actf, auto dest) __attribute__((always_inline)) {
+    constexpr int kDest = decltype(dest)::value;
+    if constexpr (kDest == 2) {
+      static_for<0, MT / MP>([&](auto pass_c) __attribute__((always_inline)) { drain32(actf, pass_c); });
+    } else {
+      drain(actf, std::integral_constant<bool, kDest == 1>());
+    }
+  };
+  auto drain_by_activation = [&](auto dest) __attribute__((always_inline)) {
     switch (act) {
-      case kActRelu: drain([](float t) { return fmaxf(t, 0.0f); }, via_lds); break;
-      case kActGeluErf: drain([](float t) { return gelu_erf_f32(t); }, via_lds); break;
-      case kActGeluTanh: drain([](float t) { return gelu_tanh_f32(t); }, via_lds); break;
-      case kActSwishScale: { const float c = p.scale; drain([c](float t) { return swish_scale_f32(t, c); }, via_lds); } break;
-      case kActSigmoidScaleResidual: { const float c = p.scale; drain([c](float t) { return sigmoid_scale_residual_f32(t, c); }, via_lds); } break;
-      default: drain([](float t) { return t; }, via_lds); break;
+      case kActRelu: drain_to([](float t) { return fmaxf(t, 0.0f); }, dest); break;
+      case kActGeluErf: drain_to([](float t) { return gelu_erf_f32(t); }, dest); break;
+      case kActGeluTanh: drain_to([](float t) { return gelu_tanh_f32(t); }, dest); break;
+      case kActSwishScale: { const float c = p.scale; drain_to([c](float t) { return swish_scale_f32(t, c); }, dest); } break;
+      case kActSigmoidScaleResidual: { const float c = p.scale; drain_to([c](float t) { return sigmoid_scale_residual_f32(t, c); }, dest); } break;
+      default: drain_to([](float t) { return t; }, dest); break;
     }
   };
 
-  if (!through_lds) {
-    drain_by_activation(std::false_type());
+  if (!through_lds && !through_lds32) {
+    drain_by_activation(std::integral_constant<int, 0>());
     return;
   }
   __builtin_amdgcn_s_barrier();                // all waves are done reading the slab stages
   asm volatile("" ::: "memory");
-  drain_by_activation(std::true_type());
+  if (through_lds32) {
+    drain_by_activation(std::integral_constant<int, 2>());
+    return;
+  }
+  drain_by_activation(std::integral_constant<int, 1>());
 
   TO* Cb = (TO*)p.C + batch * p.stride_c;
   const int slane = fresh_lane();

@@ -409,6 +409,21 @@ def test_split_plan_two_launches(g, oracle):
     assert np.array_equal(wl.to_float64(C), ref["y"])
 
 
+def test_fp32_output_of_every_mfma_tile(g, oracle):
+    """fp32 C leaves the matrix-core kernels through an LDS transpose in passes (whole-line
+    stores) when its rows are 16-byte aligned, otherwise straight from the accumulator layout:
+    both routes, ragged edges, padded rows, batches, bias + activation, every tile shape."""
+    for cfg in mfma_configs(g):
+        for (M, N, K, batch, pad_c) in [(300, 520, 136, 1, 0), (300, 520, 136, 1, 4), (257, 522, 72, 1, 0),
+                                        (130, 260, 64, 3, 0), (64, 100, 64, 1, 1)]:
+            w = wl.Workload("t", M, N, K, batch=batch, epilogue="bias_relu", seed_a=11, seed_b=12, seed_bias=13)
+            exact_case(g, oracle, w, cfg, out_dtype="f32", pad_c=pad_c)
+    for cfg in F8_CONFIGS:
+        w = wl.Workload("t", 300, 520, 256, dtype="f8", epilogue="bias_relu", seed_a=11, seed_b=12, seed_bias=13)
+        exact_case(g, oracle, w, cfg, out_dtype="f32")
+        exact_case(g, oracle, w, cfg, out_dtype="f32", pad_c=1)
+
+
 def test_tuning_mode_times_once_per_problem_and_keeps_results_exact(g, oracle):
     """Tuning mode (the paper's parameter optimisation as a switch): the first run of a problem
     times the alternatives on the caller's buffers and remembers the winner; results stay bit
