@@ -528,7 +528,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   constexpr int CH = OROWB / 16;                // 16-byte chunks per row (8, 12 or 16)
   constexpr int OSW = CH % 8 == 0 ? 7 : 3;      // chunk-slot swizzle mask: stays inside the row for CH = 12
   static_assert(Cfg::LDS_BYTES >= BM * BN * 2, "the output block must fit the slab stages");
-  static_assert(CH >= 8 && CH % 4 == 0 && (Cfg::WTM * CH) % 64 == 0,
+  static_assert(CH >= 8 && CH % 4 == 0 && (32 * CH) % 64 == 0,
                 "row of the wave block: at least 128 bytes, and the block a whole number of wave-wide accesses");
   unsigned char* wt = smem + wave * (Cfg::WTM * OROWB);
   // fp32 output goes through the same LDS pieces in passes of MP 32-row tiles (a wave's share of
@@ -590,8 +590,54 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       }
     }
   };
-  auto drain = [&](auto actf, auto via_lds) __attribute__((always_inline)) {
-    constexpr bool kViaLds = decltype(via_lds)::value;
+  // 16-bit through LDS, one 32-row tile of the wave block per pass: its rows are on their way
+  // to memory while the next tile's accumulators are drained
+  auto drain16 = [&](auto actf, auto pass_c) __attribute__((always_inline)) {
+    constexpr int m = decltype(pass_c)::value;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int j = col0 + wn * Cfg::WTN + n * 32 + g * 8 + eh * 4;
+        float bv[4];
+        bias4(j, bv);
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][g * 4 + e] + bv[e]);
+        // chunk q of row r sits at chunk slot q ^ ((r >> 1) & OSW): spreads the 32 rows
+        // a write instruction touches over the banks
+        const int r = m * 32 + er, q = n * 4 + g;
+        u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
+        *(u32x2_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & OSW)) * 16) + eh * 8) = w;
+      }
+    }
+    TO* Cb = (TO*)p.C + batch * p.stride_c;
+    const int slane = fresh_lane();
+#pragma unroll
+    for (int it = 0; it < 32 * CH / 64; ++it) {
+      // the tile's 16-byte chunks in row-major order, 64 per access: whole rows (or runs of rows)
+      const int e = it * 64 + slane;
+      const int r = m * 32 + e / CH, q = e % CH;
+      const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & OSW)) * 16));
+      const int i = row0 + wm * Cfg::WTM + r;
+      const int j = col0 + wn * Cfg::WTN + q * 8;
+      if (i < p.M && j < p.N) {
+        TO* c = Cb + (int64_t)i * p.ldc + j;
+        if (j + 8 <= p.N) {
+          __builtin_nontemporal_store(val, (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
+        } else {                                 // ragged right edge: element by element
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            const uint32_t word = val[t >> 1];
+            const uint16_t h = (t & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xffffu);
+            if (j + t < p.N) ((uint16_t*)c)[t] = h;
+          }
+        }
+      }
+    }
+  };
+  // straight from the accumulator layout (C rows that are not 16-byte aligned)
+  auto drain = [&](auto actf) __attribute__((always_inline)) {
     const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C & 15) == 0) && (p.stride_c % 4 == 0);
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
@@ -605,15 +651,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][g * 4 + e] + bv[e]);
-          if constexpr (kViaLds) {
-            // chunk q of row r sits at chunk slot q ^ ((r >> 1) & OSW): spreads the 32 rows
-            // a write instruction touches over the banks
-            const int r = m * 32 + er, q = n * 4 + g;
-            u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
-            *(u32x2_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & OSW)) * 16) + eh * 8) = w;
-          } else {
-            // fp32 output, or C rows that are not 16-byte aligned: store from the
-            // accumulator layout
+          {
             const int i = row0 + wm * Cfg::WTM + m * 32 + er;
             if (i >= p.M || j >= p.N) continue;
             const bool full = (j + 3 < p.N);
@@ -649,8 +687,10 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     constexpr int kDest = decltype(dest)::value;
     if constexpr (kDest == 2) {
       static_for<0, MT / MP>([&](auto pass_c) __attribute__((always_inline)) { drain32(actf, pass_c); });
+    } else if constexpr (kDest == 1) {
+      static_for<0, MT>([&](auto pass_c) __attribute__((always_inline)) { drain16(actf, pass_c); });
     } else {
-      drain(actf, std::integral_constant<bool, kDest == 1>());
+      drain(actf);
     }
   };
   auto drain_by_activation = [&](auto dest) __attribute__((always_inline)) {
@@ -675,31 +715,6 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     return;
   }
   drain_by_activation(std::integral_constant<int, 1>());
-
-  TO* Cb = (TO*)p.C + batch * p.stride_c;
-  const int slane = fresh_lane();
-#pragma unroll
-  for (int it = 0; it < Cfg::WTM * CH / 64; ++it) {
-    // the block's 16-byte chunks in row-major order, 64 per access: whole rows (or runs of rows)
-    const int e = it * 64 + slane;
-    const int r = e / CH, q = e % CH;
-    const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ ((r >> 1) & OSW)) * 16));
-    const int i = row0 + wm * Cfg::WTM + r;
-    const int j = col0 + wn * Cfg::WTN + q * 8;
-    if (i < p.M && j < p.N) {
-      TO* c = Cb + (int64_t)i * p.ldc + j;
-      if (j + 8 <= p.N) {
-        __builtin_nontemporal_store(val, (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
-      } else {                                 // ragged right edge: element by element
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const uint32_t word = val[e >> 1];
-          const uint16_t h = (e & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xffffu);
-          if (j + e < p.N) ((uint16_t*)c)[e] = h;
-        }
-      }
-    }
-  }
 }
 
 }  // namespace mi355gemm
