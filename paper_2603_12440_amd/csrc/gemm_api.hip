@@ -57,6 +57,7 @@ struct gemm_plan {
   // is the fastest) or 2 (`tuned`, a plan of the fastest configuration, runs instead).
   // Both are set once, with atomic operations; a plan stays shareable between threads.
   gemm_desc_t d_user;
+  int c_cached;           // fp32 C of this plan is re-read right away (the inner plan of a split-K plan)
   int built_in;
   int tune_state;
   gemm_plan* tuned;
@@ -128,6 +129,7 @@ hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* 
   a.tiles_n = (int)((d.N + BN - 1) / BN);
   a.group_m = pl.group_m;
   a.xcd_remap = pl.xcd_remap;
+  a.c_cached = pl.c_cached;
   mfma_gemm_kernel<T, TO, BM, BN, BK, WM, WN, NS><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
@@ -529,6 +531,7 @@ static int create_resolved(const gemm_desc_t& d, int config, bool allow_two_laun
   pl->splits = 0;
   pl->inner = nullptr;
   pl->d_user = d;
+  pl->c_cached = 0;
   pl->built_in = auto_choice && allow_two_launches;   // (second launches and split-K inner plans are parts, not plans)
   pl->tune_state = 0;
   pl->tuned = nullptr;
@@ -629,6 +632,8 @@ int gemm_create_splitk(const gemm_desc_t* desc, int splits, gemm_plan_t** out_pl
   gemm_plan_t* inner = nullptr;
   rc = create_resolved(in, inner_cfg, false, &inner);
   if (rc != GEMM_OK) return rc;
+  inner->c_cached = 1;                // the reduction kernel reads the partials next
+  if (inner->tail) inner->tail->c_cached = 1;
   gemm_plan* pl = new (std::nothrow) gemm_plan(*inner);
   if (!pl) { gemm_destroy(inner); return GEMM_ERR_NULL; }
   pl->d = d;

@@ -30,6 +30,7 @@ struct MfmaArgs {
   int tiles_m, tiles_n;        // ceil(M/BM), ceil(N/BN)
   int group_m;                 // tile rows per scheduling group
   int xcd_remap;               // 1: spread consecutive tile ids within one XCD
+  int c_cached;                // 1: fp32 C is read again right away (split-K partials): ordinary stores
 };
 
 // ---- MFMA wrappers -----------------------------------------------------------
@@ -581,7 +582,10 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       if (i < p.M && j < p.N) {
         float* c = Cf + (int64_t)i * p.ldc + j;
         if (j + 4 <= p.N) {
-          __builtin_nontemporal_store(val, (f32x4_t*)c);
+          // C is normally not read again here: non-temporal, so that it does not displace A and B
+          // in L2; split-K partials are read by the next kernel and should stay cached
+          if (p.c_cached) *(f32x4_t*)c = val;
+          else __builtin_nontemporal_store(val, (f32x4_t*)c);
         } else {
 #pragma unroll
           for (int t = 0; t < 4; ++t)
