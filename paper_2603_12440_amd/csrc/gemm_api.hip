@@ -457,12 +457,16 @@ int choose(const gemm_desc_t& d) {
   }
   const int best = best_mfma(d, nullptr);
   if (best >= 0) return best;
-  // general kernel: small tile for small problems so that more CUs get work
-  // (the small tile with the long K step for latency-bound problems: few trips through the
-  // load - barrier - multiply loop)
-  const int big = find_config("simt_64x64x16"), small = find_config("simt_32x32x64");
+  // general kernel: the 64x64 tile once there are two or more of them per CU (4096^3: 69 TFLOP/s against
+  // 34 with 32x32 tiles, 1536^3: 175 us against 233 us; 1024^3, one 64x64 tile per CU: 127 us against 76 us), otherwise the small
+  // tile so that more workgroups share a CU; for very few tiles the small tile with the long K
+  // step (latency-bound: few trips through the load - barrier - multiply loop)
+  const int big = find_config("simt_64x64x16"), small = find_config("simt_32x32x16"),
+            small_long = find_config("simt_32x32x64");
   const double tiles64 = (double)((d.M + 63) / 64) * (double)((d.N + 63) / 64) * d.batch;
-  return tiles64 >= kNumCUs ? big : small;
+  const double tiles32 = (double)((d.M + 31) / 32) * (double)((d.N + 31) / 32) * d.batch;
+  if (tiles64 >= 2.0 * kNumCUs) return big;
+  return tiles32 <= 2.0 * kNumCUs ? small_long : small;
 }
 
 int fill_launch_shape(gemm_plan& pl) {

@@ -225,7 +225,10 @@ def test_kernel_choice(g):
     assert "grid=256,1,1" in kernel(M=1, N=8192, K=8192)
     assert "kernel=mfma8_256x256x128" in kernel(M=8192, N=8192, K=8192, dtype=g.F8E4M3)
     assert "kernel=mfma8_" in kernel(M=4, N=8192, K=8192, dtype=g.F8E4M3)      # no skinny fp8 kernel
-    assert "kernel=simt" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=simt_32x32x64" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=simt_32x32x16" in kernel(M=1024, N=1024, K=1024, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=simt_64x64x16" in kernel(M=4096, N=4096, K=4096, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=simt_64x64x16" in kernel(M=1536, N=1536, K=1536, dtype=g.F32, layout_b=g.ROW_MAJOR)
     # 16-bit operands the tiled kernels cannot take go to the general kernel
     assert "kernel=simt" in kernel(M=256, N=256, K=256, layout_a=g.COL_MAJOR)
     assert "kernel=simt" in kernel(M=256, N=256, K=100)            # K not a multiple of 8
