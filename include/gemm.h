@@ -108,7 +108,8 @@ typedef struct {
  * gemm_run A and B must be 16-byte aligned (GEMM_ERR_MISALIGNED otherwise).  M <= 16 goes to
  * the HBM-bound skinny kernels, everything else to the tiled MFMA kernel.  Every other
  * combination (fp32 operands, other layouts, odd leading dimensions) is served by the general
- * fp32-FMA kernel, which needs element alignment only; fp8 operands have no such fallback
+ * true-fp32 kernels (vector-ALU FMA for small problems, the fp32 matrix-core instruction
+ * otherwise), which need element alignment only; fp8 operands have no such fallback
  * (GEMM_ERR_UNSUPPORTED).
  */
 

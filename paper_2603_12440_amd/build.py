@@ -8,8 +8,10 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmi355gemm.so")
-SOURCES = [os.path.join(CSRC, "gemm_api.hip"), os.path.join(CSRC, "rope_api.hip"),
-           os.path.join(CSRC, "probe_api.hip")]
+SOURCES = [os.path.join(CSRC, f) for f in
+           ("gemm_api.hip", "mfma_bf16_inst.hip", "mfma_f16_inst.hip", "mfma_f8_inst.hip",
+            "rope_api.hip", "probe_api.hip")]
+OBJ_DIR = os.path.join(os.path.dirname(HERE), "_build")
 
 
 def _hipcc() -> str:
@@ -31,25 +33,43 @@ def sources_newer_than_lib() -> bool:
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile every kernel instantiation for gfx950 into one shared library."""
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           # packed-fp32 VALU forms stay off
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-function", "-o", LIB] + SOURCES
-    cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
-    res = subprocess.run(cmd, capture_output=True, text=True)
+    """Compile every kernel instantiation for gfx950 (one object per translation unit, side by
+    side) and link them into one shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+             # packed-fp32 VALU forms stay off
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage"]
     noise = ("is not a recognized feature for this target", "-Rpass-analysis=kernel-resource-usage")
-    err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
-    bad = kernels_with_scratch(res.stderr)
+
+    def compile_one(src):
+        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        res = subprocess.run([_hipcc()] + flags + ["-c", src, "-o", obj], capture_output=True, text=True)
+        return src, obj, res
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+        results = list(pool.map(compile_one, SOURCES))
+    objs, remarks = [], []
+    for src, obj, res in results:
+        err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {os.path.basename(src)}:\n" + err)
+        if verbose and err.strip():
+            print(err)
+        objs.append(obj)
+        remarks.append(res.stderr)
+    bad = kernels_with_scratch("\n".join(remarks))
     if bad:
-        os.remove(LIB)
+        if os.path.exists(LIB):
+            os.remove(LIB)
         raise RuntimeError("kernels that keep data in scratch memory (the hand-scheduled kernels place their own "
                            "waits for asynchronous LDS reads and matrix-core results; a register the compiler "
                            "moves to memory in between breaks that):\n  " + "\n  ".join(bad))
+    res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs,
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("linking failed:\n" + res.stderr)
     return LIB
 
 

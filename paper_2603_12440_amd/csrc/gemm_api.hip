@@ -19,65 +19,27 @@
 
 #include "../../include/gemm.h"
 #include "common.hpp"
-#include "mfma_kernel.hpp"
+#include "plan.hpp"
+#include "mfma_launch.hpp"
 #include "simt_kernel.hpp"
+#include "general_mfma_kernel.hpp"
 #include "skinny_kernel.hpp"
 #include "splitk_kernel.hpp"
 #include "device_check.hpp"
 
 using namespace mi355gemm;
 
-namespace {
-
-enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_MFMA = 3, KIND_SKINNY_RING = 4 };
-// (KIND_SKINNY_RING also covers the register-staged kernel: same panel shape, grid and limits)
-
-struct Config;
-
-}  // namespace
-
-struct gemm_plan {
-  gemm_desc_t d;          // fully resolved (no zero ld / stride left)
-  const Config* cfg;
-  int cfg_index;
-  dim3 grid, block;
-  int group_m, xcd_remap; // MFMA scheduling
-  // Optional second launch for the columns past d.N (a different tile shape for the part of
-  // the problem that does not fill whole rounds of the CUs): its own plan, and the element
-  // offsets of its B, C and bias.
-  gemm_plan* tail;
-  int64_t tail_off_b, tail_off_c, tail_off_bias;
-  // Split-K: `d` is the caller's problem, `inner` the batched product of the K slices into
-  // the fp32 workspace (cfg, grid, ... above are then those of the inner plan, for reporting).
-  int splits;
-  gemm_plan* inner;
-  // Tuning mode (gemm_set_autotune / GEMM_TUNE=1): `d_user` is the caller's resolved problem
-  // (d may have been narrowed to the first launch's columns), `built_in` says the kernel was
-  // the library's choice, and once the problem has been timed `tune_state` is 1 (this plan
-  // is the fastest) or 2 (`tuned`, a plan of the fastest configuration, runs instead).
-  // Both are set once, with atomic operations; a plan stays shareable between threads.
-  gemm_desc_t d_user;
-  int c_cached;           // fp32 C of this plan is re-read right away (the inner plan of a split-K plan)
-  int built_in;
-  int tune_state;
-  gemm_plan* tuned;
-};
+namespace mi355gemm {
+#define X(BM, BN, BK, WM, WN, NS) MI355GEMM_MFMA_DECLARE(bf16_t, bf16_t, BM, BN, BK, WM, WN, NS) \
+                                 MI355GEMM_MFMA_DECLARE(f16_t, f16_t, BM, BN, BK, WM, WN, NS)
+MI355GEMM_MFMA_TILES(X)
+#undef X
+#define X(BM, BN, BK, WM, WN, NS) MI355GEMM_MFMA_DECLARE(f8e4m3_t, bf16_t, BM, BN, BK, WM, WN, NS)
+MI355GEMM_MFMA8_TILES(X)
+#undef X
+}  // namespace mi355gemm
 
 namespace {
-
-typedef hipError_t (*launch_fn)(const gemm_plan&, const void*, const void*, void*, const void*,
-                                hipStream_t);
-
-struct Config {
-  const char* name;
-  Kind kind;
-  int bm, bn, bk;         // tile (skinny: bm = padded M, bn = workgroups per CU, bk = K per pass)
-  int threads;
-  int lds_bytes;
-  launch_fn launch[4];    // per operand dtype (GEMM_F32 / BF16 / F16 / F8E4M3); NULL = not compiled
-};
-
-inline int esize(int dt) { return dt == GEMM_F32 ? 4 : (dt == GEMM_F8E4M3 ? 1 : 2); }
 
 // ---- launchers ---------------------------------------------------------------------
 
@@ -103,35 +65,42 @@ hipError_t launch_simt_typed(const gemm_plan& pl, const void* A, const void* B, 
   return hipGetLastError();
 }
 
+template <typename TIn, typename TOut, int TM, int TN, int TK>
+hipError_t launch_general_mfma_typed(const gemm_plan& pl, const void* A, const void* B, void* C,
+                                     const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  SimtArgs a;
+  a.A = A; a.B = B; a.C = C; a.bias = (const float*)bias;
+  a.M = d.M; a.N = d.N; a.K = d.K;
+  a.a_si = d.layout_a == GEMM_ROW_MAJOR ? d.lda : 1;
+  a.a_sk = d.layout_a == GEMM_ROW_MAJOR ? 1 : d.lda;
+  a.b_sk = d.layout_b == GEMM_ROW_MAJOR ? d.ldb : 1;
+  a.b_sj = d.layout_b == GEMM_ROW_MAJOR ? 1 : d.ldb;
+  a.c_si = d.layout_c == GEMM_ROW_MAJOR ? d.ldc : 1;
+  a.c_sj = d.layout_c == GEMM_ROW_MAJOR ? 1 : d.ldc;
+  a.stride_a = d.stride_a; a.stride_b = d.stride_b; a.stride_c = d.stride_c;
+  a.stride_bias = d.stride_bias;
+  a.has_bias = epilogue_has_bias(d.epilogue);
+  a.act = epilogue_activation(d.epilogue);
+  a.scale = d.scale;
+  general_mfma_kernel<TIn, TOut, TM, TN, TK><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+template <typename TIn, int TM, int TN, int TK>
+hipError_t launch_general_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
+                               const void* bias, hipStream_t s) {
+  if (pl.d.dtype_c == GEMM_F32)
+    return launch_general_mfma_typed<TIn, float, TM, TN, TK>(pl, A, B, C, bias, s);
+  return launch_general_mfma_typed<TIn, TIn, TM, TN, TK>(pl, A, B, C, bias, s);
+}
+
 template <typename TIn, int TM, int TN, int TK>
 hipError_t launch_simt(const gemm_plan& pl, const void* A, const void* B, void* C,
                        const void* bias, hipStream_t s) {
   if (pl.d.dtype_c == GEMM_F32)
     return launch_simt_typed<TIn, float, TM, TN, TK>(pl, A, B, C, bias, s);
   return launch_simt_typed<TIn, TIn, TM, TN, TK>(pl, A, B, C, bias, s);
-}
-
-template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int NS>
-hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
-                       const void* bias, hipStream_t s) {
-  const gemm_desc_t& d = pl.d;
-  MfmaArgs a;
-  a.A = A; a.B = B; a.C = C; a.bias = (const float*)bias;
-  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
-  a.lda = d.lda; a.ldb = d.ldb; a.ldc = d.ldc;
-  a.stride_a = d.stride_a; a.stride_b = d.stride_b; a.stride_c = d.stride_c;
-  a.stride_bias = d.stride_bias;
-  a.has_bias = epilogue_has_bias(d.epilogue);
-  a.act = epilogue_activation(d.epilogue);
-  a.scale = d.scale;
-  a.c_f32 = d.dtype_c == GEMM_F32;
-  a.tiles_m = (int)((d.M + BM - 1) / BM);
-  a.tiles_n = (int)((d.N + BN - 1) / BN);
-  a.group_m = pl.group_m;
-  a.xcd_remap = pl.xcd_remap;
-  a.c_cached = pl.c_cached;
-  mfma_gemm_kernel<T, TO, BM, BN, BK, WM, WN, NS><<<pl.grid, pl.block, 0, s>>>(a);
-  return hipGetLastError();
 }
 
 template <typename T, int MB, int WAVES>
@@ -214,6 +183,13 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
     { launch_simt<float, TM, TN, TK>, launch_simt<bf16_t, TM, TN, TK>,                     \
       launch_simt<f16_t, TM, TN, TK> } }
 
+// the general kernel on the matrix cores (fp32 MFMA): same problems, same grid as SIMT_CFG
+#define GENERAL_MFMA_CFG(TM, TN, TK)                                                       \
+  { "general_mfma32_" #TM "x" #TN "x" #TK, KIND_SIMT, TM, TN, TK, 256,                     \
+    (int)(sizeof(float) * TK * (TM + 4 + TN + 4)),                                         \
+    { launch_general_mfma<float, TM, TN, TK>, launch_general_mfma<bf16_t, TM, TN, TK>,     \
+      launch_general_mfma<f16_t, TM, TN, TK> } }
+
 #define MFMA_CFG(BM, BN, BK, WM, WN, NS)                                                   \
   { "mfma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, KIND_MFMA, BM, BN, BK,          \
     64 * WM * WN, MfmaTile<bf16_t, BM, BN, BK, WM, WN, NS>::LDS_BYTES,                     \
@@ -262,6 +238,8 @@ const Config kConfigs[] = {
     MFMA8_CFG(256, 256, 128, 2, 4, 2),
     MFMA8_CFG(128, 128, 128, 2, 2, 2),
     MFMA8_CFG(256, 192, 128, 4, 2, 2),
+    GENERAL_MFMA_CFG(128, 128, 16),
+    GENERAL_MFMA_CFG(64, 64, 16),
     SKINNY_CFG(1, 4, 1),
     SKINNY_CFG(2, 4, 1),
     SKINNY_CFG(4, 4, 1),
@@ -457,16 +435,16 @@ int choose(const gemm_desc_t& d) {
   }
   const int best = best_mfma(d, nullptr);
   if (best >= 0) return best;
-  // general kernel: the 64x64 tile once there are two or more of them per CU (4096^3: 69 TFLOP/s against
-  // 34 with 32x32 tiles, 1536^3: 175 us against 233 us; 1024^3, one 64x64 tile per CU: 127 us against 76 us), otherwise the small
-  // tile so that more workgroups share a CU; for very few tiles the small tile with the long K
-  // step (latency-bound: few trips through the load - barrier - multiply loop)
-  const int big = find_config("simt_64x64x16"), small = find_config("simt_32x32x16"),
-            small_long = find_config("simt_32x32x64");
-  const double tiles64 = (double)((d.M + 63) / 64) * (double)((d.N + 63) / 64) * d.batch;
+  // general kernels (fp32 operands, or layouts / leading dimensions the tiled kernels do not
+  // take).  Very few tiles: the vector-ALU kernel with 32x32 tiles and the long K step (latency
+  // bound: 256^3 11 us, 512^3 19 us; the matrix-core kernel needs 16 / 28 us there).  Otherwise the
+  // fp32-MFMA kernel: 64x64 tiles (1024^3: 53 us against 76 us on the vector ALUs, 2048^3: 212
+  // against 293 us) until there are four 128x128 tiles per CU (4096^3: 1.47 ms = 93 TFLOP/s
+  // against 2.00 ms).
   const double tiles32 = (double)((d.M + 31) / 32) * (double)((d.N + 31) / 32) * d.batch;
-  if (tiles64 >= 2.0 * kNumCUs) return big;
-  return tiles32 <= 2.0 * kNumCUs ? small_long : small;
+  const double tiles128 = (double)((d.M + 127) / 128) * (double)((d.N + 127) / 128) * d.batch;
+  if (tiles32 <= 2.0 * kNumCUs) return find_config("simt_32x32x64");
+  return find_config(tiles128 >= 4.0 * kNumCUs ? "general_mfma32_128x128x16" : "general_mfma32_64x64x16");
 }
 
 int fill_launch_shape(gemm_plan& pl) {

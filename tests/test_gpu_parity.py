@@ -98,9 +98,13 @@ def test_skinny_exact_small_integers(g, oracle, M):
 @pytest.mark.parametrize("la,lb,lc", [("row", "row", "row"), ("row", "col", "row"), ("col", "row", "col"),
                                       ("col", "col", "row"), ("row", "row", "col")])
 def test_general_kernel_exact_all_layouts(g, oracle, dtype, la, lb, lc):
-    for cfg in ("simt_64x64x16", "simt_32x32x16"):
+    for cfg in ("simt_64x64x16", "simt_32x32x16", "general_mfma32_128x128x16", "general_mfma32_64x64x16"):
         w = wl.Workload("t", 70, 130, 45, dtype=dtype, layout_a=la, layout_b=lb, seed_a=3, seed_b=4)
         exact_case(g, oracle, w, cfg, layout_c=lc, pad_a=1, pad_b=2, pad_c=3)
+    # several tiles of the matrix-core general kernel in both directions, ragged edges, K tail
+    w = wl.Workload("t", 300, 260, 70, dtype=dtype, layout_a=la, layout_b=lb, epilogue="bias_relu",
+                    seed_a=8, seed_b=9, seed_bias=10)
+    exact_case(g, oracle, w, "general_mfma32_128x128x16", layout_c=lc, pad_a=3, pad_c=1)
     w = wl.Workload("t", 65, 33, 19, dtype=dtype, layout_a=la, layout_b=lb, batch=3,
                     epilogue="bias", seed_a=5, seed_b=6, seed_bias=7)
     exact_case(g, oracle, w, None, layout_c=lc, out_dtype="f32")
@@ -217,7 +221,7 @@ def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
                            (16, 100, 1032, "skinnystage_d3_b256"), (7, 70, 264, "skinnystage_d2_b512"),
                            (11, 40, 2120, "skinnystage_d2_b256"), (16, 100, 1032, "skinnystage_d2_b256_w8"),
                            (6, 70, 3128, "skinnystage_d2_b256_w8"),
-                           (70, 90, 50, "simt_64x64x16")]:
+                           (70, 90, 50, "simt_64x64x16"), (150, 140, 50, "general_mfma32_128x128x16")]:
         # pre-activations of order 1 so that the activations' curved parts are exercised
         w = wl.Workload("t", M, N, K, dist_a=("normal", 1.0), dist_b=("normal", 1.5 / np.sqrt(K)),
                         epilogue=epilogue, dist_bias=("uniform", 1.0), seed_a=11, seed_b=12, seed_bias=13,
@@ -283,7 +287,7 @@ def test_fp32_config_full_size(g, oracle):
     w = wl.WORKLOADS["f32_256"]
     A, B, _ = wl.make_inputs(w)
     ref = run_oracle(oracle, w, A, B, None)
-    for cfg in (None, "simt_64x64x16", "simt_32x32x16"):
+    for cfg in (None, "simt_64x64x16", "simt_32x32x16", "general_mfma32_128x128x16", "general_mfma32_64x64x16"):
         say(f"f32_256 cfg={cfg}")
         C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg) if cfg else -1)
         r = assert_parity(w, C, ref, A, B, None)
@@ -355,7 +359,7 @@ def test_tuner_times_every_applicable_configuration(g, oracle):
     names = g.config_names()
     assert names[best] in times and times[names[best]] == min(times.values())
     assert all(t > 0 for t in times.values())
-    assert {n for n in names if n.startswith("mfma_") or n.startswith("simt")} == set(times)   # M = 300: no skinny, no fp8
+    assert {n for n in names if n.startswith(("mfma_", "simt", "general_"))} == set(times)   # M = 300: no skinny, no fp8
     plan = g.gemm_create_config(desc, best)
     g.gemm_run(plan, Ad, Bd, Cd, bd)
     torch.cuda.synchronize()
