@@ -278,7 +278,7 @@ def bench_rope(args, g, dev):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1",
+        print("bench.py measures one GPU only (the library has no multi-GPU path); run with --gpus 1",
               file=sys.stderr)
         return 2
     import paper_2603_12440_amd as g
