@@ -21,6 +21,7 @@
 #include "common.hpp"
 #include "plan.hpp"
 #include "mfma_launch.hpp"
+#include "mfma16_launch.hpp"
 #include "simt_kernel.hpp"
 #include "general_mfma_kernel.hpp"
 #include "skinny_kernel.hpp"
@@ -36,6 +37,10 @@ MI355GEMM_MFMA_TILES(X)
 #undef X
 #define X(BM, BN, BK, WM, WN, NS) MI355GEMM_MFMA_DECLARE(f8e4m3_t, bf16_t, BM, BN, BK, WM, WN, NS)
 MI355GEMM_MFMA8_TILES(X)
+#undef X
+#define X(BM, BN, WM, WN, G) MI355GEMM_MFMA16_DECLARE(bf16_t, bf16_t, BM, BN, WM, WN, G) \
+                             MI355GEMM_MFMA16_DECLARE(f16_t, f16_t, BM, BN, WM, WN, G)
+MI355GEMM_MFMA16_TILES(X)
 #undef X
 }  // namespace mi355gemm
 
@@ -195,6 +200,12 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
     64 * WM * WN, MfmaTile<bf16_t, BM, BN, BK, WM, WN, NS>::LDS_BYTES,                     \
     { nullptr, launch_mfma<bf16_t, bf16_t, BM, BN, BK, WM, WN, NS>,                        \
       launch_mfma<f16_t, f16_t, BM, BN, BK, WM, WN, NS> } }
+// the same product on the 16x16x32 MFMA shape (slabs of 64 columns of K, two stages)
+#define MFMA16_CFG(BM, BN, WM, WN, G)                                                      \
+  { "mfma16_" #BM "x" #BN "x64_w" #WM "x" #WN, KIND_MFMA, BM, BN, 64,                      \
+    64 * WM * WN, Mfma16Tile<bf16_t, BM, BN, WM, WN, G>::LDS_BYTES,                        \
+    { nullptr, launch_mfma16<bf16_t, bf16_t, BM, BN, WM, WN, G>,                           \
+      launch_mfma16<f16_t, f16_t, BM, BN, WM, WN, G> } }
 // fp8 (E4M3) operands, bf16 or fp32 output: the same slabs in bytes (BK is twice as many values)
 #define MFMA8_CFG(BM, BN, BK, WM, WN, NS)                                                  \
   { "mfma8_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, KIND_MFMA, BM, BN, BK,         \
@@ -228,6 +239,9 @@ const Config kConfigs[] = {
     SIMT_CFG(64, 64, 16),
     SIMT_CFG(32, 32, 16),
     SIMT_CFG(32, 32, 64),
+    MFMA16_CFG(256, 256, 2, 4, 2),
+    MFMA16_CFG(256, 256, 2, 2, 2),
+    MFMA16_CFG(128, 128, 2, 2, 2),
     MFMA_CFG(256, 256, 64, 2, 4, 2),
     MFMA_CFG(256, 256, 64, 2, 2, 2),
     MFMA_CFG(256, 256, 32, 2, 2, 4),
@@ -361,7 +375,10 @@ double mfma_cost(const Config& c, int64_t M, int64_t N, int64_t K, int64_t batch
   const int area = c.bm * c.bn;
   const int per_cu = area <= 128 * 128 ? 2 : 1;                 // workgroups that fit one CU's LDS
   // (256x192 measured: 0.85 - 1.03 of the 256x256 tile per FLOP on 4096x6144x4096, 4096x14336x4096, 8192^3)
-  const double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 192 ? 0.88 : (area >= 256 * 128 ? 0.75 : 0.84));
+  double eff = area >= 256 * 256 ? 1.0 : (area >= 256 * 192 ? 0.88 : (area >= 256 * 128 ? 0.75 : 0.84));
+  // the 16x16x32 kernels: about a tenth faster per FLOP than the 32x32x16 ones at the same tile shape
+  // (8192^3: 732 against 800 us); of the two 256x256 shapes the eight-wave one goes first
+  if (!std::strncmp(c.name, "mfma16_", 7)) eff *= c.threads == 256 && area >= 256 * 256 ? 1.08 : 1.10;
   const double tiles = (double)((M + c.bm - 1) / c.bm) * (double)((N + c.bn - 1) / c.bn) * (double)batch;
   const double rounds = (double)(int64_t)((tiles + kNumCUs * per_cu - 1) / (kNumCUs * per_cu));
   // workgroups that actually share a CU (a lone workgroup runs about per_cu times faster)

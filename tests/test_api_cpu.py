@@ -65,7 +65,7 @@ def test_probe_argument_checks_need_no_device(g):
 def test_splitk_plans(g):
     """Split-K planning is host work: slices, workspace size, what it refuses."""
     p = g.gemm_create_splitk(g.GemmDesc(512, 512, 32768))
-    assert "kernel=splitk_16+mfma_128x128" in p.info() and "grid=16,16,1" in p.info()
+    assert "kernel=splitk_16+mfma16_128x128" in p.info() and "grid=16,16,1" in p.info()
     assert g.gemm_workspace_bytes(p) == 16 * 512 * 512 * 4
     # a split-K plan cannot run without its workspace
     with pytest.raises(g.GemmError) as e:
@@ -205,15 +205,16 @@ def test_kernel_choice(g):
         info = p.info()
         g.gemm_destroy(p)
         return info
-    assert "kernel=mfma_256x256" in kernel(M=8192, N=8192, K=8192)
+    assert "kernel=mfma16_256x256x64_w2x4" in kernel(M=8192, N=8192, K=8192)
     assert "grid=1024,1,1" in kernel(M=8192, N=8192, K=8192)
-    # wave quantisation: 384 tiles of 256x256 are 1.5 rounds of the 256 CUs, 512 tiles of 256x192 two full ones
-    assert "kernel=mfma_256x192x64_w4x2_s2" in kernel(M=4096, N=6144, K=4096)
-    assert "grid=512,1,1" in kernel(M=4096, N=6144, K=4096)
-    assert "kernel=mfma_256x256" in kernel(M=4096, N=4096, K=14336)
+    # wave quantisation: 384 tiles of 256x256 are 1.5 rounds of the 256 CUs: one whole round on the big
+    # tile, the remaining third of the columns as a second launch
+    q = kernel(M=4096, N=6144, K=4096)
+    assert "kernel=mfma16_256x256" in q and "grid=256,1,1" in q and "columns=4096.." in q
+    assert "kernel=mfma16_256x256" in kernel(M=4096, N=4096, K=14336)
     # one round and an eighth: the whole round on the big tile, the rest as a second launch
     two = kernel(M=4096, N=4608, K=4096)
-    assert "kernel=mfma_256x256" in two and "columns=0..4095" in two and "columns=4096.." in two
+    assert "kernel=mfma16_256x256" in two and "columns=0..4095" in two and "columns=4096.." in two
     for m in (1, 4):
         assert "kernel=skinny_m" in kernel(M=m, N=8192, K=8192)
     assert "kernel=skinny_m1_w8_g1" in kernel(M=1, N=8192, K=8192)

@@ -31,7 +31,7 @@ def cfg_index(g, name):
 
 
 def mfma_configs(g):
-    return [n for n in g.config_names() if n.startswith("mfma_")]
+    return [n for n in g.config_names() if n.startswith(("mfma_", "mfma16_"))]
 
 
 def skinny_configs(g, m):
@@ -359,7 +359,7 @@ def test_tuner_times_every_applicable_configuration(g, oracle):
     names = g.config_names()
     assert names[best] in times and times[names[best]] == min(times.values())
     assert all(t > 0 for t in times.values())
-    assert {n for n in names if n.startswith(("mfma_", "simt", "general_"))} == set(times)   # M = 300: no skinny, no fp8
+    assert {n for n in names if n.startswith(("mfma_", "mfma16_", "simt", "general_"))} == set(times)   # M = 300: no skinny, no fp8
     plan = g.gemm_create_config(desc, best)
     g.gemm_run(plan, Ad, Bd, Cd, bd)
     torch.cuda.synchronize()
