@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmi355gemm.so")
 SOURCES = [os.path.join(CSRC, f) for f in
            ("gemm_api.hip", "mfma_bf16_inst.hip", "mfma_f16_inst.hip", "mfma_f8_inst.hip",
-            "mfma16_bf16_inst.hip", "mfma16_f16_inst.hip", "rope_api.hip", "probe_api.hip")]
+            "mfma16_bf16_inst.hip", "mfma16_f16_inst.hip", "mfma16p_bf16_inst.hip", "mfma16p_f16_inst.hip", "rope_api.hip", "probe_api.hip")]
 OBJ_DIR = os.path.join(os.path.dirname(HERE), "_build")
 
 

@@ -38,9 +38,10 @@ MI355GEMM_MFMA_TILES(X)
 #define X(BM, BN, BK, WM, WN, NS) MI355GEMM_MFMA_DECLARE(f8e4m3_t, bf16_t, BM, BN, BK, WM, WN, NS)
 MI355GEMM_MFMA8_TILES(X)
 #undef X
-#define X(BM, BN, WM, WN, G) MI355GEMM_MFMA16_DECLARE(bf16_t, bf16_t, BM, BN, WM, WN, G) \
-                             MI355GEMM_MFMA16_DECLARE(f16_t, f16_t, BM, BN, WM, WN, G)
+#define X(BM, BN, WM, WN, G, P) MI355GEMM_MFMA16_DECLARE(bf16_t, bf16_t, BM, BN, WM, WN, G, P) \
+                                MI355GEMM_MFMA16_DECLARE(f16_t, f16_t, BM, BN, WM, WN, G, P)
 MI355GEMM_MFMA16_TILES(X)
+MI355GEMM_MFMA16P_TILES(X)
 #undef X
 }  // namespace mi355gemm
 
@@ -204,8 +205,16 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
 #define MFMA16_CFG(BM, BN, WM, WN, G)                                                      \
   { "mfma16_" #BM "x" #BN "x64_w" #WM "x" #WN, KIND_MFMA, BM, BN, 64,                      \
     64 * WM * WN, Mfma16Tile<bf16_t, BM, BN, WM, WN, G>::LDS_BYTES,                        \
-    { nullptr, launch_mfma16<bf16_t, bf16_t, BM, BN, WM, WN, G>,                           \
-      launch_mfma16<f16_t, f16_t, BM, BN, WM, WN, G> } }
+    { nullptr, launch_mfma16<bf16_t, bf16_t, BM, BN, WM, WN, G, false>,                    \
+      launch_mfma16<f16_t, f16_t, BM, BN, WM, WN, G, false> }, 0 }
+// persistent workgroups (K a whole number of slabs, at least two): the grid is the number of
+// workgroups the chip holds at once, each walks over its share of the tiles
+#define MFMA16P_CFG(BM, BN, WM, WN, G)                                                     \
+  { "mfma16_" #BM "x" #BN "x64_w" #WM "x" #WN "_p", KIND_MFMA, BM, BN, 64,                 \
+    64 * WM * WN, Mfma16Tile<bf16_t, BM, BN, WM, WN, G>::LDS_BYTES +                       \
+                      Mfma16Tile<bf16_t, BM, BN, WM, WN, G>::EPI_BYTES,                    \
+    { nullptr, launch_mfma16<bf16_t, bf16_t, BM, BN, WM, WN, G, true>,                     \
+      launch_mfma16<f16_t, f16_t, BM, BN, WM, WN, G, true> }, 1 }
 // fp8 (E4M3) operands, bf16 or fp32 output: the same slabs in bytes (BK is twice as many values)
 #define MFMA8_CFG(BM, BN, BK, WM, WN, NS)                                                  \
   { "mfma8_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, KIND_MFMA, BM, BN, BK,         \
@@ -239,6 +248,9 @@ const Config kConfigs[] = {
     SIMT_CFG(64, 64, 16),
     SIMT_CFG(32, 32, 16),
     SIMT_CFG(32, 32, 64),
+    MFMA16P_CFG(256, 256, 2, 4, 2),
+    MFMA16P_CFG(256, 256, 2, 2, 2),
+    MFMA16P_CFG(128, 128, 2, 2, 2),
     MFMA16_CFG(256, 256, 2, 4, 2),
     MFMA16_CFG(256, 256, 2, 2, 2),
     MFMA16_CFG(128, 128, 2, 2, 2),
@@ -357,6 +369,7 @@ bool applicable(const Config& c, const gemm_desc_t& d) {
   if ((int64_t)c.bm * d.lda * esize(d.dtype_a) >= ((int64_t)1 << 32) ||
       (int64_t)c.bn * d.ldb * esize(d.dtype_a) >= ((int64_t)1 << 32))
     return false;
+  if (c.persist && (d.K % c.bk != 0 || d.K < 2 * c.bk)) return false;   // whole slabs, at least two
   const int64_t tiles = ((d.M + c.bm - 1) / c.bm) * ((d.N + c.bn - 1) / c.bn);
   return tiles < ((int64_t)1 << 31);
 }
@@ -476,7 +489,12 @@ int fill_launch_shape(gemm_plan& pl) {
     pl.grid = dim3((unsigned)gx, (unsigned)gy, (unsigned)d.batch);
   } else if (c.kind == KIND_MFMA) {
     const int64_t tm = (d.M + c.bm - 1) / c.bm, tn = (d.N + c.bn - 1) / c.bn;
-    pl.grid = dim3((unsigned)(tm * tn), (unsigned)d.batch, 1);
+    int64_t wgs = tm * tn;
+    if (c.persist) {                           // as many workgroups as run at once; each takes every wgs-th tile
+      const int64_t at_once = (int64_t)kNumCUs * (160 * 1024 / c.lds_bytes);
+      if (wgs > at_once) wgs = at_once;
+    }
+    pl.grid = dim3((unsigned)wgs, (unsigned)d.batch, 1);
     pl.group_m = (int)(tm < 8 ? tm : 8);
     pl.xcd_remap = ((tm * tn) % 8 == 0) ? 1 : 0;
   } else if (c.kind == KIND_SKINNY_RING) {

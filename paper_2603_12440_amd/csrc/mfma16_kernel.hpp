@@ -113,57 +113,72 @@ struct Mfma16Tile {
   static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+  // the epilogue's staging area of a persistent workgroup: one 16-row band of every wave's block in fp32
+  static constexpr int EPI_BYTES = kWaves * 16 * WTN * 4;
   static_assert(sizeof(T) == 2, "16-bit operands");
   static_assert(BM % (RPI * kWaves) == 0 && BN % (RPI * kWaves) == 0, "slab rows must divide over waves");
   static_assert(WTM % 16 == 0 && WTN % 16 == 0 && MT % G == 0, "wave block in whole sub-steps");
   static_assert(NSUB % 2 == 0, "the row-fragment double buffer alternates per sub-step");
   static_assert(MA * NT >= MA + NT, "a sub-step issues one fragment read behind each MFMA");
-  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+  static_assert(LDS_BYTES + EPI_BYTES <= 160 * 1024, "LDS budget");
 };
 
 // T: operand type; TO: the 16-bit output type (outputs may also be fp32: MfmaArgs::c_f32).
-template <typename T, typename TO, int BM, int BN, int WM, int WN, int G>
+// PERSIST: a workgroup walks over several tiles (tile ids blockIdx.x, blockIdx.x + gridDim.x,
+// ...) as one software pipeline: the slabs of the next tile are requested while the last slabs
+// of the current one are multiplied, and land while its epilogue runs, which stages C through an
+// LDS region of its own.  Needs K to be a whole number of slabs, at least two.
+template <typename T, typename TO, int BM, int BN, int WM, int WN, int G, bool PERSIST>
 __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   typedef Mfma16Tile<T, BM, BN, WM, WN, G> Cfg;
   constexpr int MT = Cfg::MT, NT = Cfg::NT, MA = Cfg::MA, CPR = Cfg::CPR, RPI = Cfg::RPI;
   constexpr int ROWB = Cfg::ROWB, BK = Cfg::BK, KK = Cfg::KK, NSUB = Cfg::NSUB;
   constexpr bool kTwoPerSimd = Cfg::kWaves > 4;          // two waves share a SIMD: alternate by priority
 
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[Cfg::LDS_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[Cfg::LDS_BYTES + (PERSIST ? Cfg::EPI_BYTES : 0)];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
-
-  int tm, tn;
-  tile_coords(p, blockIdx.x, gridDim.x, tm, tn);
-  const int row0 = tm * BM, col0 = tn * BN;
   const int64_t batch = blockIdx.y;
-
-  const T* Ab = (const T*)p.A + batch * p.stride_a + (int64_t)row0 * p.lda;
-  const T* Bb = (const T*)p.B + batch * p.stride_b + (int64_t)col0 * p.ldb;
+  const int n_tiles = p.tiles_m * p.tiles_n;
 
   // ---- global -> LDS addressing (as in mfma_kernel.hpp, with this kernel's swizzle) -------
   // Load q of this wave fills LDS bytes [slab + (wave*LOADS + q)*1024, +1024): lane l writes
   // 16 bytes at +16*l, i.e. slab row (wave*LOADS+q)*RPI + l/CPR, slot l%CPR, which must
   // receive logical chunk slot ^ swz16(row).  Rows past the matrix edge are clamped to the
   // last valid row (their results are never stored).
+  // The tile the loads work on (it runs ahead of the tile being multiplied):
+  const char* ld_a;                              // first byte of the next slab to request, A and B
+  const char* ld_b;
   uint32_t a_off[Cfg::A_LOADS], b_off[Cfg::B_LOADS];
+  // (`ln`: the lane id; a persistent workgroup recomputes the offsets from a fresh copy of it after
+  // each epilogue, so that they need not stay in registers across it.)  Leaves ld_a / ld_b at slab `kt`.
+  auto load_tile = [&](int vid, int ln, int kt) __attribute__((always_inline)) {
+    int tm, tn;
+    tile_coords(p, vid, n_tiles, tm, tn);
+    const int r0 = tm * BM, c0 = tn * BN;
+    ld_a = (const char*)((const T*)p.A + batch * p.stride_a + (int64_t)r0 * p.lda) + (int64_t)kt * ROWB;
+    ld_b = (const char*)((const T*)p.B + batch * p.stride_b + (int64_t)c0 * p.ldb) + (int64_t)kt * ROWB;
 #pragma unroll
-  for (int q = 0; q < Cfg::A_LOADS; ++q) {
-    const int r = (wave * Cfg::A_LOADS + q) * RPI + lane / CPR;
-    const int c = (lane % CPR) ^ swz16(r);
-    const int rr = min(r, p.M - 1 - row0);
-    a_off[q] = (uint32_t)(((int64_t)rr * p.lda + c * 8) * 2);
-  }
+    for (int q = 0; q < Cfg::A_LOADS; ++q) {
+      const int r = (wave * Cfg::A_LOADS + q) * RPI + ln / CPR;
+      const int c = (ln % CPR) ^ swz16(r);
+      const int rr = min(r, p.M - 1 - r0);
+      a_off[q] = (uint32_t)(((int64_t)rr * p.lda + c * 8) * 2);
+    }
 #pragma unroll
-  for (int q = 0; q < Cfg::B_LOADS; ++q) {
-    const int r = (wave * Cfg::B_LOADS + q) * RPI + lane / CPR;
-    const int c = (lane % CPR) ^ swz16(r);
-    const int rr = min(r, p.N - 1 - col0);
-    b_off[q] = (uint32_t)(((int64_t)rr * p.ldb + c * 8) * 2);
-  }
+    for (int q = 0; q < Cfg::B_LOADS; ++q) {
+      const int r = (wave * Cfg::B_LOADS + q) * RPI + ln / CPR;
+      const int c = (ln % CPR) ^ swz16(r);
+      const int rr = min(r, p.N - 1 - c0);
+      b_off[q] = (uint32_t)(((int64_t)rr * p.ldb + c * 8) * 2);
+    }
+  };
+  load_tile(blockIdx.x, lane, 0);
+  const char* const Ab = ld_a;                   // (the first tile's panels: the one-tile path indexes them by slab)
+  const char* const Bb = ld_b;
 
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_uchar_t*)smem;
   constexpr int kLoads = Cfg::A_LOADS + Cfg::B_LOADS;
@@ -177,14 +192,17 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gv);
     return (const char*)(((uint64_t)hi << 32) | (uint64_t)lo);
   };
-  auto slab_io = [&](int kt, int st) __attribute__((always_inline)) {
+  auto slab_io_at = [&](const char* ga, const char* gb, int st) __attribute__((always_inline)) {
     SlabIo io;
-    io.ga = uniform_ptr((const char*)Ab + (int64_t)kt * ROWB);
-    io.gb = uniform_ptr((const char*)Bb + (int64_t)kt * ROWB);
+    io.ga = uniform_ptr(ga);
+    io.gb = uniform_ptr(gb);
     io.la = (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + st * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024)));
     io.lb = (uint32_t)__builtin_amdgcn_readfirstlane(
         (int)(lds_base + st * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024)));
     return io;
+  };
+  auto slab_io = [&](int kt, int st) __attribute__((always_inline)) {
+    return slab_io_at(Ab + (int64_t)kt * ROWB, Bb + (int64_t)kt * ROWB, st);
   };
   // One direct-to-LDS load (scalar base + 32-bit lane offset; M0 = LDS destination of the wave,
   // lane l lands at M0 + 16*l): q < A_LOADS fills the A slab, the rest the B slab.  M0 is written
@@ -205,8 +223,8 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   // slab goes through registers.  (K is a multiple of 8: chunks are never split.)
   auto issue_loads_tail = [&](int kt, int stage) __attribute__((always_inline)) {
     const int kvalid = p.K - kt * BK;
-    const char* ga = (const char*)Ab + (int64_t)kt * ROWB;
-    const char* gb = (const char*)Bb + (int64_t)kt * ROWB;
+    const char* ga = Ab + (int64_t)kt * ROWB;
+    const char* gb = Bb + (int64_t)kt * ROWB;
     unsigned char* sa = smem + stage * Cfg::STAGE_BYTES + wave * (Cfg::A_LOADS * 1024);
     unsigned char* sb = smem + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (Cfg::B_LOADS * 1024);
 #pragma unroll
@@ -232,17 +250,22 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   // step's four.  Fragment m of the wave is 16*m rows further on: a constant offset.  The
   // address registers point into the stage being read and move to the other stage at each
   // hand-over (one vector add each), so a fragment read needs no address arithmetic.
-  const int fr = lane & 15, fo = lane >> 4;
-  const int a_row = wm * Cfg::WTM + fr;
-  const int b_row = wn * Cfg::WTN + fr;
   uint32_t a_rd[KK], b_rd[KK];
+  int rd_delta;                                  // to the other stage (alternates in sign)
+  // point the address registers into stage `st` (`ln`: the lane id, see load_tile)
+  auto set_read_stage = [&](int st, int ln) __attribute__((always_inline)) {
+    const int fr = ln & 15, fo = ln >> 4;
+    const int a_row = wm * Cfg::WTM + fr;
+    const int b_row = wn * Cfg::WTN + fr;
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    const int c = kk * 4 + fo;
-    a_rd[kk] = lds_base + a_row * ROWB + ((c ^ swz16(a_row)) * 16);
-    b_rd[kk] = lds_base + Cfg::A_BYTES + b_row * ROWB + ((c ^ swz16(b_row)) * 16);
-  }
-  int rd_delta = Cfg::STAGE_BYTES;               // to the other stage (alternates in sign)
+    for (int kk = 0; kk < KK; ++kk) {
+      const int c = kk * 4 + fo;
+      a_rd[kk] = lds_base + st * Cfg::STAGE_BYTES + a_row * ROWB + ((c ^ swz16(a_row)) * 16);
+      b_rd[kk] = lds_base + st * Cfg::STAGE_BYTES + Cfg::A_BYTES + b_row * ROWB + ((c ^ swz16(b_row)) * 16);
+    }
+    rd_delta = st ? -Cfg::STAGE_BYTES : Cfg::STAGE_BYTES;
+  };
+  set_read_stage(0, lane);
   auto flip_read_stage = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) { a_rd[kk] += rd_delta; b_rd[kk] += rd_delta; }
@@ -282,7 +305,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   // request than every MFMA before it); with `reads`, the requests for the next sub-step go out
   // one behind each of the first MFMAs; loads q0 .. q1-1 of the slab `io` are spaced evenly
   // over the MFMAs.
-  auto sub_step = [&](auto u_c, bool reads, int q0, int q1, const SlabIo& io) __attribute__((always_inline)) {
+  auto sub_step = [&](auto u_c, bool reads, int q0, int q1, const SlabIo& io, bool do_loads = true) __attribute__((always_inline)) {
     constexpr int u = decltype(u_c)::value;
     constexpr int kk = u / G, g = u % G;
     constexpr int un = (u + 1) % NSUB;                    // the sub-step the reads are for
@@ -303,7 +326,9 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
       if (reads && i < OrdN::kReads) read_one(std::integral_constant<int, un>(), i);
 #pragma unroll
       for (int j = 0; j < nq; ++j)
-        if ((int)((j + 0.5f) * Ord::kMfma / nq) == i) issue_one_load(q0 + j, io);
+        if ((int)((j + 0.5f) * Ord::kMfma / nq) == i) {
+          if (do_loads) issue_one_load(q0 + j, io);      // (a wave-uniform branch around one statement)
+        }
     }
   };
   auto set_prio = [&](int pr) __attribute__((always_inline)) {
@@ -314,6 +339,231 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
       case 2: __builtin_amdgcn_s_setprio(2); break;
       default: __builtin_amdgcn_s_setprio(3); break;
     }
+  };
+
+  // ---- epilogue of the tile at (row0, col0) ---------------------------------------------------
+  auto epilogue = [&](int row0, int col0) __attribute__((always_inline)) {
+    // What the epilogue needs of the arguments.  A persistent workgroup reads them from the argument
+    // block again for every tile (the kernel's only argument sits at the start of the kernarg segment),
+    // so that they do not occupy scalar registers during the K loops.
+    typedef __attribute__((address_space(4))) const volatile MfmaArgs kernarg_t;
+    MfmaArgs pe = p;
+    if constexpr (PERSIST) {
+      kernarg_t* pv = (kernarg_t*)__builtin_amdgcn_kernarg_segment_ptr();
+      pe.C = pv->C; pe.bias = pv->bias; pe.M = pv->M; pe.N = pv->N; pe.ldc = pv->ldc; pe.stride_c = pv->stride_c;
+      pe.stride_bias = pv->stride_bias; pe.has_bias = pv->has_bias; pe.act = pv->act; pe.c_f32 = pv->c_f32;
+      pe.c_cached = pv->c_cached; pe.scale = pv->scale;
+    }
+    // The MFMAs were issued through inline assembly: the compiler inserts none of the wait states
+    // a vector-ALU read of a just-written MFMA result needs.  Wait once, and route every
+    // accumulator through an (empty) volatile statement placed after the wait.
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+      for (int n = 0; n < NT; ++n) asm volatile("" : "+a"(acc[m][n]));
+
+    // ---- epilogue ---------------------------------------------------------------------------
+    // Lane l of a 16x16 accumulator tile holds row (l % 16) and, in its four registers, columns
+    // 4*(l / 16) .. +3 (the operands go in swapped, column fragment first).  For whole-line
+    // stores each wave passes one 16-row band of its block at a time through its own piece of
+    // the (now idle) LDS: 8- or 16-byte writes in accumulator order, 16-byte reads in row order.
+    const float* bias = pe.has_bias ? pe.bias + batch * pe.stride_bias : nullptr;
+    const int act = pe.act;
+    auto fresh_lane = []() __attribute__((always_inline)) {
+      unsigned z = 0;
+      asm volatile("" : "+v"(z));
+      return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, z));
+    };
+    const int elane = fresh_lane();
+    const int er = elane & 15, eq = elane >> 4;
+
+    // bias of the 4 columns j .. j+3 (zero past N; j is a multiple of 4); 16-byte loads only when the
+    // bias vector of this batch starts at a 16-byte aligned address (the same for every lane)
+    const bool bias_vec = (((uintptr_t)bias) & 15) == 0;
+    auto bias4 = [&](int j, float (&bv)[4]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bv[e] = 0.0f;
+      if (!bias) return;
+      if (j + 3 < pe.N && bias_vec) {
+        const f32x4_t b4 = *(const f32x4_t*)(bias + j);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bv[e] = b4[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (j + e < pe.N) bv[e] = bias[j + e];
+      }
+    };
+
+    const bool through_lds = !pe.c_f32 && (pe.ldc % 8 == 0) && (pe.stride_c % 8 == 0) &&
+                             (((uintptr_t)pe.C & 15) == 0);
+    const bool through_lds32 = pe.c_f32 && (pe.ldc % 4 == 0) && (pe.stride_c % 4 == 0) && (((uintptr_t)pe.C & 15) == 0);
+    constexpr int OROWB = Cfg::WTN * 2;           // bytes per 16-bit row of the wave's block (128 or 256)
+    constexpr int CH = OROWB / 16;
+    constexpr int OROWB32 = Cfg::WTN * 4;         // bytes per fp32 row (256 or 512)
+    constexpr int CH32 = OROWB32 / 16;
+    constexpr int kShare = Cfg::LDS_BYTES / Cfg::kWaves;
+    static_assert(16 * OROWB32 <= kShare, "one 16-row band of the wave block in fp32 must fit the wave's share of LDS");
+    static_assert(OROWB == 128 || OROWB == 256, "staging rows of 128 or 256 bytes");
+    // staging: this wave's share of the idle slab stages, or of the separate area of a persistent workgroup
+    unsigned char* wt = PERSIST ? smem + Cfg::LDS_BYTES + wave * (Cfg::EPI_BYTES / Cfg::kWaves) : smem + wave * kShare;
+    // chunk-slot key of staging row r: 128-byte rows alternate between the two halves of the banks,
+    // longer rows all start at bank 0
+    auto osw = [](int r) __attribute__((always_inline)) { return OROWB == 128 ? ((r >> 1) & 7) : (r & 15); };
+
+    // 16-bit through LDS, band m
+    auto drain16 = [&](auto actf, auto m_c) __attribute__((always_inline)) {
+      constexpr int m = decltype(m_c)::value;
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
+        float bv[4];
+        bias4(j, bv);
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][e] + bv[e]);
+        const int q = n * 2 + (eq >> 1);
+        u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
+        *(u32x2_t*)(wt + er * OROWB + ((q ^ osw(er)) * 16) + (eq & 1) * 8) = w;
+      }
+      TO* Cb = (TO*)pe.C + batch * pe.stride_c;
+      const int slane = fresh_lane();
+#pragma unroll
+      for (int it = 0; it < 16 * CH / 64; ++it) {
+        const int e = it * 64 + slane;
+        const int r = e / CH, q = e % CH;
+        const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ osw(r)) * 16));
+        const int i = row0 + wm * Cfg::WTM + m * 16 + r;
+        const int j = col0 + wn * Cfg::WTN + q * 8;
+        if (i < pe.M && j < pe.N) {
+          TO* c = Cb + (int64_t)i * pe.ldc + j;
+          if (j + 8 <= pe.N) {
+            __builtin_nontemporal_store(val, (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
+          } else {                                 // ragged right edge: element by element
+#pragma unroll
+            for (int t2 = 0; t2 < 8; ++t2) {
+              const uint32_t word = val[t2 >> 1];
+              const uint16_t h = (t2 & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xffffu);
+              if (j + t2 < pe.N) ((uint16_t*)c)[t2] = h;
+            }
+          }
+        }
+      }
+    };
+    // fp32 through LDS, band m
+    auto drain32 = [&](auto actf, auto m_c) __attribute__((always_inline)) {
+      constexpr int m = decltype(m_c)::value;
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
+        float bv[4];
+        bias4(j, bv);
+        f32x4_t w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = actf(acc[m][n][e] + bv[e]);
+        const int q = n * 4 + eq;
+        *(f32x4_t*)(wt + er * OROWB32 + ((q ^ (er & 15)) * 16)) = w;
+      }
+      float* Cf = (float*)pe.C + batch * pe.stride_c;
+      const int slane = fresh_lane();
+#pragma unroll
+      for (int it = 0; it < 16 * CH32 / 64; ++it) {
+        const int e = it * 64 + slane;
+        const int r = e / CH32, q = e % CH32;
+        const f32x4_t val = *(const f32x4_t*)(wt + r * OROWB32 + ((q ^ (r & 15)) * 16));
+        const int i = row0 + wm * Cfg::WTM + m * 16 + r;
+        const int j = col0 + wn * Cfg::WTN + q * 4;
+        if (i < pe.M && j < pe.N) {
+          float* c = Cf + (int64_t)i * pe.ldc + j;
+          if (j + 4 <= pe.N) {
+            if (pe.c_cached) *(f32x4_t*)c = val;    // split-K partials are read by the next kernel
+            else __builtin_nontemporal_store(val, (f32x4_t*)c);
+          } else {
+#pragma unroll
+            for (int t2 = 0; t2 < 4; ++t2)
+              if (j + t2 < pe.N) c[t2] = val[t2];
+          }
+        }
+      }
+    };
+    // straight from the accumulator layout (C rows that are not 16-byte aligned)
+    auto drain = [&](auto actf) __attribute__((always_inline)) {
+      const bool vec_ok = (pe.ldc % 4 == 0) && (((uintptr_t)pe.C & 15) == 0) && (pe.stride_c % 4 == 0);
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
+        float bv[4];
+        bias4(j, bv);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][e] + bv[e]);
+          const int i = row0 + wm * Cfg::WTM + m * 16 + er;
+          if (i >= pe.M || j >= pe.N) continue;
+          const bool full = (j + 3 < pe.N);
+          const int64_t o = batch * pe.stride_c + (int64_t)i * pe.ldc + j;
+          if (pe.c_f32) {
+            float* c = (float*)pe.C + o;
+            if (full && vec_ok) {
+              f32x4_t w = {v[0], v[1], v[2], v[3]};
+              *(f32x4_t*)c = w;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (j + e < pe.N) c[e] = v[e];
+            }
+          } else {
+            TO* c = (TO*)pe.C + o;
+            if (full && vec_ok) {
+              u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
+              *(u32x2_t*)c = w;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (j + e < pe.N) c[e] = from_float<TO>(v[e]);
+            }
+          }
+        }
+      }
+    };
+    // dest: 0 = memory from the accumulator layout, 1 = 16-bit through LDS, 2 = fp32 through LDS
+    auto drain_to = [&](auto actf, auto dest) __attribute__((always_inline)) {
+      constexpr int kDest = decltype(dest)::value;
+      if constexpr (kDest == 2) {
+        static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) { drain32(actf, m_c); });
+      } else if constexpr (kDest == 1) {
+        static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) { drain16(actf, m_c); });
+      } else {
+        drain(actf);
+      }
+    };
+    auto drain_by_activation = [&](auto dest) __attribute__((always_inline)) {
+      switch (act) {
+        case kActRelu: drain_to([](float x) { return fmaxf(x, 0.0f); }, dest); break;
+        case kActGeluErf: drain_to([](float x) { return gelu_erf_f32(x); }, dest); break;
+        case kActGeluTanh: drain_to([](float x) { return gelu_tanh_f32(x); }, dest); break;
+        case kActSwishScale: { const float c = pe.scale; drain_to([c](float x) { return swish_scale_f32(x, c); }, dest); } break;
+        case kActSigmoidScaleResidual: { const float c = pe.scale; drain_to([c](float x) { return sigmoid_scale_residual_f32(x, c); }, dest); } break;
+        default: drain_to([](float x) { return x; }, dest); break;
+      }
+    };
+
+    if (!through_lds && !through_lds32) {
+      // (a persistent workgroup is only launched for C rows that take the staged routes below)
+      if constexpr (!PERSIST) drain_by_activation(std::integral_constant<int, 0>());
+      return;
+    }
+    if constexpr (!PERSIST) {
+      __builtin_amdgcn_s_barrier();              // all waves are done reading the slab stages
+      asm volatile("" ::: "memory");
+    }
+    if (through_lds32) {
+      drain_by_activation(std::integral_constant<int, 2>());
+      return;
+    }
+    drain_by_activation(std::integral_constant<int, 1>());
   };
 
   // ---- main loop ------------------------------------------------------------------------
@@ -356,6 +606,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   typedef std::integral_constant<bool, true> yes_t;
   typedef std::integral_constant<bool, false> no_t;
 
+  if constexpr (!PERSIST) {
   if (T_full > 0) {
     {
       const SlabIo io0 = slab_io(0, 0);
@@ -399,211 +650,102 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     });
     wait_lgkmcnt<0>();
   }
-
-  // The MFMAs were issued through inline assembly: the compiler inserts none of the wait states
-  // a vector-ALU read of a just-written MFMA result needs.  Wait once, and route every
-  // accumulator through an (empty) volatile statement placed after the wait.
-  asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-#pragma unroll
-  for (int m = 0; m < MT; ++m)
-#pragma unroll
-    for (int n = 0; n < NT; ++n) asm volatile("" : "+a"(acc[m][n]));
-
-  // ---- epilogue ---------------------------------------------------------------------------
-  // Lane l of a 16x16 accumulator tile holds row (l % 16) and, in its four registers, columns
-  // 4*(l / 16) .. +3 (the operands go in swapped, column fragment first).  For whole-line
-  // stores each wave passes one 16-row band of its block at a time through its own piece of
-  // the (now idle) LDS: 8- or 16-byte writes in accumulator order, 16-byte reads in row order.
-  const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
-  const int act = p.act;
-  auto fresh_lane = []() __attribute__((always_inline)) {
+  int tm, tn;
+  tile_coords(p, blockIdx.x, n_tiles, tm, tn);
+  epilogue(tm * BM, tn * BN);
+  } else {
+  // ---- persistent: the tiles of this workgroup as one stream of slabs ------------------------
+  // The loads run two slabs ahead of the MFMAs and simply carry on into the next tile's panels:
+  // every slab body but the last two of the last tile requests loads.  ld_a / ld_b and the lane
+  // offsets describe the slab the loads are at; they move on one slab at a time and switch to
+  // the next tile when this one's slabs are all requested.
+  int ld_vid = blockIdx.x, ld_t = 0;
+  auto fresh_lane_id = []() __attribute__((always_inline)) {
     unsigned z = 0;
     asm volatile("" : "+v"(z));
     return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, z));
   };
-  const int elane = fresh_lane();
-  const int er = elane & 15, eq = elane >> 4;
-
-  // bias of the 4 columns j .. j+3 (zero past N); 16-byte load only from a 16-byte aligned address
-  auto bias4 = [&](int j, float (&bv)[4]) __attribute__((always_inline)) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) bv[e] = 0.0f;
-    if (!bias) return;
-    if (j + 3 < p.N && (((uintptr_t)(bias + j)) & 15) == 0) {
-      const f32x4_t b4 = *(const f32x4_t*)(bias + j);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) bv[e] = b4[e];
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (j + e < p.N) bv[e] = bias[j + e];
+  auto next_slab = [&]() __attribute__((always_inline)) {
+    ld_a += ROWB; ld_b += ROWB;
+    if (++ld_t == T_full) {
+      ld_t = 0;
+      ld_vid += gridDim.x;
+      if (ld_vid < n_tiles) load_tile(ld_vid, fresh_lane_id(), 0);   // (no lane id kept in a register across the loop)
     }
   };
-
-  const bool through_lds = !p.c_f32 && (p.ldc % 8 == 0) && (p.stride_c % 8 == 0) &&
-                           (((uintptr_t)p.C & 15) == 0);
-  const bool through_lds32 = p.c_f32 && (p.ldc % 4 == 0) && (p.stride_c % 4 == 0) && (((uintptr_t)p.C & 15) == 0);
-  constexpr int OROWB = Cfg::WTN * 2;           // bytes per 16-bit row of the wave's block (128 or 256)
-  constexpr int CH = OROWB / 16;
-  constexpr int OROWB32 = Cfg::WTN * 4;         // bytes per fp32 row (256 or 512)
-  constexpr int CH32 = OROWB32 / 16;
-  constexpr int kShare = Cfg::LDS_BYTES / Cfg::kWaves;
-  static_assert(16 * OROWB32 <= kShare, "one 16-row band of the wave block in fp32 must fit the wave's share of LDS");
-  static_assert(OROWB == 128 || OROWB == 256, "staging rows of 128 or 256 bytes");
-  unsigned char* wt = smem + wave * kShare;
-  // chunk-slot key of staging row r: 128-byte rows alternate between the two halves of the banks,
-  // longer rows all start at bank 0
-  auto osw = [](int r) __attribute__((always_inline)) { return OROWB == 128 ? ((r >> 1) & 7) : (r & 15); };
-
-  // 16-bit through LDS, band m
-  auto drain16 = [&](auto actf, auto m_c) __attribute__((always_inline)) {
-    constexpr int m = decltype(m_c)::value;
-#pragma unroll
-    for (int n = 0; n < NT; ++n) {
-      const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
-      float bv[4];
-      bias4(j, bv);
-      float v[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][e] + bv[e]);
-      const int q = n * 2 + (eq >> 1);
-      u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
-      *(u32x2_t*)(wt + er * OROWB + ((q ^ osw(er)) * 16) + (eq & 1) * 8) = w;
-    }
-    TO* Cb = (TO*)p.C + batch * p.stride_c;
-    const int slane = fresh_lane();
-#pragma unroll
-    for (int it = 0; it < 16 * CH / 64; ++it) {
-      const int e = it * 64 + slane;
-      const int r = e / CH, q = e % CH;
-      const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ osw(r)) * 16));
-      const int i = row0 + wm * Cfg::WTM + m * 16 + r;
-      const int j = col0 + wn * Cfg::WTN + q * 8;
-      if (i < p.M && j < p.N) {
-        TO* c = Cb + (int64_t)i * p.ldc + j;
-        if (j + 8 <= p.N) {
-          __builtin_nontemporal_store(val, (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
-        } else {                                 // ragged right edge: element by element
-#pragma unroll
-          for (int t2 = 0; t2 < 8; ++t2) {
-            const uint32_t word = val[t2 >> 1];
-            const uint16_t h = (t2 & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xffffu);
-            if (j + t2 < p.N) ((uint16_t*)c)[t2] = h;
-          }
-        }
-      }
-    }
+  // tile_end (compile time): the last slab of a tile; its last sub-step requests no fragments (the
+  // next tile's first ones are read after the epilogue, which then has no fragment registers to
+  // keep alive).  early / late (run time; true in every slab but the last two of the last tile):
+  // whether the rest of one slab's loads and the first part of the next one's are requested.
+  auto body = [&](auto end_c, bool early, bool late) __attribute__((always_inline)) {
+    constexpr bool tile_end = decltype(end_c)::value;
+    const SlabIo io_early = slab_io_at(ld_a, ld_b, stage ^ 1);
+    static_for<0, NSUB - 1>([&](auto u_c) __attribute__((always_inline)) {
+      constexpr int u = decltype(u_c)::value;
+      set_prio(u < 3 ? 2 - u : 0);
+      constexpr int q0 = kLoads * (u + 1) / LW, q1 = kLoads * (u + 2) / LW;
+      if constexpr (u + 1 < LW)
+        sub_step(u_c, true, q0 < kLoads ? q0 : kLoads, q1 < kLoads ? q1 : kLoads, io_early, early);
+      else
+        sub_step(u_c, true, 0, 0, io_none);
+    });
+    if (late) next_slab();                     // the early part was the rest of a slab: on to the next one
+    const SlabIo io_late = slab_io_at(ld_a, ld_b, stage);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    set_prio(3);
+    flip_read_stage();
+    sub_step(std::integral_constant<int, NSUB - 1>(), !tile_end, 0, kLoads / LW, io_late, late);
+    stage ^= 1;
   };
-  // fp32 through LDS, band m
-  auto drain32 = [&](auto actf, auto m_c) __attribute__((always_inline)) {
-    constexpr int m = decltype(m_c)::value;
+  // slab 0 whole and the first part of slab 1; from then on every body requests the rest of one
+  // slab and the first part of the next
+  {
+    const SlabIo io0 = slab_io_at(ld_a, ld_b, 0);
 #pragma unroll
-    for (int n = 0; n < NT; ++n) {
-      const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
-      float bv[4];
-      bias4(j, bv);
-      f32x4_t w;
+    for (int q = 0; q < kLoads; ++q) issue_one_load(q, io0);
+    next_slab();
+    const SlabIo io1 = slab_io_at(ld_a, ld_b, 1);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) w[e] = actf(acc[m][n][e] + bv[e]);
-      const int q = n * 4 + eq;
-      *(f32x4_t*)(wt + er * OROWB32 + ((q ^ (er & 15)) * 16)) = w;
-    }
-    float* Cf = (float*)p.C + batch * p.stride_c;
-    const int slane = fresh_lane();
-#pragma unroll
-    for (int it = 0; it < 16 * CH32 / 64; ++it) {
-      const int e = it * 64 + slane;
-      const int r = e / CH32, q = e % CH32;
-      const f32x4_t val = *(const f32x4_t*)(wt + r * OROWB32 + ((q ^ (r & 15)) * 16));
-      const int i = row0 + wm * Cfg::WTM + m * 16 + r;
-      const int j = col0 + wn * Cfg::WTN + q * 4;
-      if (i < p.M && j < p.N) {
-        float* c = Cf + (int64_t)i * p.ldc + j;
-        if (j + 4 <= p.N) {
-          if (p.c_cached) *(f32x4_t*)c = val;    // split-K partials are read by the next kernel
-          else __builtin_nontemporal_store(val, (f32x4_t*)c);
-        } else {
-#pragma unroll
-          for (int t2 = 0; t2 < 4; ++t2)
-            if (j + t2 < p.N) c[t2] = val[t2];
-        }
-      }
-    }
-  };
-  // straight from the accumulator layout (C rows that are not 16-byte aligned)
-  auto drain = [&](auto actf) __attribute__((always_inline)) {
-    const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C & 15) == 0) && (p.stride_c % 4 == 0);
-#pragma unroll
-    for (int n = 0; n < NT; ++n) {
-      const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
-      float bv[4];
-      bias4(j, bv);
-#pragma unroll
-      for (int m = 0; m < MT; ++m) {
-        float v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][e] + bv[e]);
-        const int i = row0 + wm * Cfg::WTM + m * 16 + er;
-        if (i >= p.M || j >= p.N) continue;
-        const bool full = (j + 3 < p.N);
-        const int64_t o = batch * p.stride_c + (int64_t)i * p.ldc + j;
-        if (p.c_f32) {
-          float* c = (float*)p.C + o;
-          if (full && vec_ok) {
-            f32x4_t w = {v[0], v[1], v[2], v[3]};
-            *(f32x4_t*)c = w;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (j + e < p.N) c[e] = v[e];
-          }
-        } else {
-          TO* c = (TO*)p.C + o;
-          if (full && vec_ok) {
-            u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
-            *(u32x2_t*)c = w;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (j + e < p.N) c[e] = from_float<TO>(v[e]);
-          }
-        }
-      }
-    }
-  };
-  // dest: 0 = memory from the accumulator layout, 1 = 16-bit through LDS, 2 = fp32 through LDS
-  auto drain_to = [&](auto actf, auto dest) __attribute__((always_inline)) {
-    constexpr int kDest = decltype(dest)::value;
-    if constexpr (kDest == 2) {
-      static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) { drain32(actf, m_c); });
-    } else if constexpr (kDest == 1) {
-      static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) { drain16(actf, m_c); });
-    } else {
-      drain(actf);
-    }
-  };
-  auto drain_by_activation = [&](auto dest) __attribute__((always_inline)) {
-    switch (act) {
-      case kActRelu: drain_to([](float x) { return fmaxf(x, 0.0f); }, dest); break;
-      case kActGeluErf: drain_to([](float x) { return gelu_erf_f32(x); }, dest); break;
-      case kActGeluTanh: drain_to([](float x) { return gelu_tanh_f32(x); }, dest); break;
-      case kActSwishScale: { const float c = p.scale; drain_to([c](float x) { return swish_scale_f32(x, c); }, dest); } break;
-      case kActSigmoidScaleResidual: { const float c = p.scale; drain_to([c](float x) { return sigmoid_scale_residual_f32(x, c); }, dest); } break;
-      default: drain_to([](float x) { return x; }, dest); break;
-    }
-  };
-
-  if (!through_lds && !through_lds32) {
-    drain_by_activation(std::integral_constant<int, 0>());
-    return;
+    for (int q = 0; q < kLoads / LW; ++q) issue_one_load(q, io1);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads / LW) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   }
-  __builtin_amdgcn_s_barrier();                // all waves are done reading the slab stages
-  asm volatile("" ::: "memory");
-  if (through_lds32) {
-    drain_by_activation(std::integral_constant<int, 2>());
-    return;
+  for (int vid = blockIdx.x; vid < n_tiles; vid += gridDim.x) {
+    const bool last = vid + (int)gridDim.x >= n_tiles;
+    read_all(std::integral_constant<int, 0>());
+    for (t = 0; t < T_full - 2; ++t) body(no_t(), true, true);
+    body(no_t(), true, !last);
+    body(yes_t(), !last, !last);
+    set_prio(0);
+    wait_lgkmcnt<0>();
+    int tm, tn;
+    tile_coords(p, vid, n_tiles, tm, tn);
+    epilogue(tm * BM, tn * BN);
+    if (!last) {
+      // the lane-dependent offsets and addresses are derived afresh here (from an opaque copy of the
+      // lane id, so that the compiler cannot keep the earlier ones alive across the epilogue instead)
+      const int lane_now = fresh_lane_id();
+      load_tile(ld_vid, lane_now, ld_t);
+      set_read_stage(stage, lane_now);
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[m][n][r] = 0.0f;
+      // (the next MFMAs are assembly statements the compiler's hazard recogniser cannot see: give the
+      // accumulator writes above time to retire, and keep them above this point)
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) asm volatile("" : "+a"(acc[m][n]));
+      asm volatile("s_nop 7" ::: "memory");
+    }
   }
-  drain_by_activation(std::integral_constant<int, 1>());
+  }
 }
 
 }  // namespace mi355gemm

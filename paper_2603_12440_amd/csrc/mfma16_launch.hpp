@@ -8,7 +8,7 @@
 
 namespace mi355gemm {
 
-template <typename T, typename TO, int BM, int BN, int WM, int WN, int G>
+template <typename T, typename TO, int BM, int BN, int WM, int WN, int G, bool PERSIST>
 hipError_t launch_mfma16(const gemm_plan& pl, const void* A, const void* B, void* C,
                          const void* bias, hipStream_t s) {
   const gemm_desc_t& d = pl.d;
@@ -27,21 +27,37 @@ hipError_t launch_mfma16(const gemm_plan& pl, const void* A, const void* B, void
   a.group_m = pl.group_m;
   a.xcd_remap = pl.xcd_remap;
   a.c_cached = pl.c_cached;
-  mfma16_gemm_kernel<T, TO, BM, BN, WM, WN, G><<<pl.grid, pl.block, 0, s>>>(a);
+  if constexpr (PERSIST) {
+    // The persistent kernel only has the staged output routes (whole-line stores): C rows that are
+    // not 16-byte aligned run one tile per workgroup instead.
+    const int64_t unit = a.c_f32 ? 4 : 8;
+    const bool staged = d.ldc % unit == 0 && d.stride_c % unit == 0 && ((uintptr_t)C & 15) == 0;
+    if (!staged) {
+      const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), pl.grid.y, 1);
+      mfma16_gemm_kernel<T, TO, BM, BN, WM, WN, G, false><<<grid, pl.block, 0, s>>>(a);
+      return hipGetLastError();
+    }
+  }
+  mfma16_gemm_kernel<T, TO, BM, BN, WM, WN, G, PERSIST><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
 
-// X(BM, BN, WM, WN, G): tile, wave grid, sub-steps per k-step (slabs of 64 columns of K, two stages)
+// X(BM, BN, WM, WN, G, PERSIST): tile, wave grid, sub-steps per k-step (slabs of 64 columns of K, two
+// stages), one tile per workgroup or a persistent workgroup walking over several
 #define MI355GEMM_MFMA16_TILES(X) \
-  X(256, 256, 2, 4, 2)            \
-  X(256, 256, 2, 2, 2)            \
-  X(128, 128, 2, 2, 2)
+  X(256, 256, 2, 4, 2, false)     \
+  X(256, 256, 2, 2, 2, false)     \
+  X(128, 128, 2, 2, 2, false)
+#define MI355GEMM_MFMA16P_TILES(X) \
+  X(256, 256, 2, 4, 2, true)       \
+  X(256, 256, 2, 2, 2, true)       \
+  X(128, 128, 2, 2, 2, true)
 
-#define MI355GEMM_MFMA16_DECLARE(T, TO, BM, BN, WM, WN, G)                                  \
-  extern template hipError_t launch_mfma16<T, TO, BM, BN, WM, WN, G>(                         \
+#define MI355GEMM_MFMA16_DECLARE(T, TO, BM, BN, WM, WN, G, P)                               \
+  extern template hipError_t launch_mfma16<T, TO, BM, BN, WM, WN, G, P>(                      \
       const gemm_plan&, const void*, const void*, void*, const void*, hipStream_t);
-#define MI355GEMM_MFMA16_DEFINE(T, TO, BM, BN, WM, WN, G)                                   \
-  template hipError_t launch_mfma16<T, TO, BM, BN, WM, WN, G>(                                \
+#define MI355GEMM_MFMA16_DEFINE(T, TO, BM, BN, WM, WN, G, P)                                \
+  template hipError_t launch_mfma16<T, TO, BM, BN, WM, WN, G, P>(                             \
       const gemm_plan&, const void*, const void*, void*, const void*, hipStream_t);
 
 }  // namespace mi355gemm

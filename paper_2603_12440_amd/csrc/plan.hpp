@@ -57,6 +57,7 @@ struct Config {
   int threads;
   int lds_bytes;
   launch_fn launch[4];    // per operand dtype (GEMM_F32 / BF16 / F16 / F8E4M3); NULL = not compiled
+  int persist;            // 1: workgroups walk over several tiles (grid = workgroups resident at once)
 };
 
 inline int esize(int dt) { return dt == GEMM_F32 ? 4 : (dt == GEMM_F8E4M3 ? 1 : 2); }

@@ -206,7 +206,8 @@ def test_kernel_choice(g):
         g.gemm_destroy(p)
         return info
     assert "kernel=mfma16_256x256x64_w2x4" in kernel(M=8192, N=8192, K=8192)
-    assert "grid=1024,1,1" in kernel(M=8192, N=8192, K=8192)
+    assert "_p " in kernel(M=8192, N=8192, K=8192) and "grid=256,1,1" in kernel(M=8192, N=8192, K=8192)   # persistent workgroups
+    assert "_p " not in kernel(M=8192, N=8192, K=8200) and "grid=1024,1,1" in kernel(M=8192, N=8192, K=8200)
     # wave quantisation: 384 tiles of 256x256 are 1.5 rounds of the 256 CUs: one whole round on the big
     # tile, the remaining third of the columns as a second launch
     q = kernel(M=4096, N=6144, K=4096)

@@ -31,7 +31,13 @@ def cfg_index(g, name):
 
 
 def mfma_configs(g):
-    return [n for n in g.config_names() if n.startswith(("mfma_", "mfma16_"))]
+    """The matrix-core tile configurations that take any K (one tile per workgroup)."""
+    return [n for n in g.config_names() if n.startswith(("mfma_", "mfma16_")) and not n.endswith("_p")]
+
+
+def persistent_configs(g):
+    """The persistent-workgroup configurations (K a whole number of 64-column slabs, at least two)."""
+    return [n for n in g.config_names() if n.startswith("mfma16_") and n.endswith("_p")]
 
 
 def skinny_configs(g, m):
@@ -359,7 +365,8 @@ def test_tuner_times_every_applicable_configuration(g, oracle):
     names = g.config_names()
     assert names[best] in times and times[names[best]] == min(times.values())
     assert all(t > 0 for t in times.values())
-    assert {n for n in names if n.startswith(("mfma_", "mfma16_", "simt", "general_"))} == set(times)   # M = 300: no skinny, no fp8
+    # M = 300: no skinny, no fp8; K = 264 is not a whole number of slabs: no persistent workgroups
+    assert {n for n in names if n.startswith(("mfma_", "mfma16_", "simt", "general_")) and not n.endswith("_p")} == set(times)
     plan = g.gemm_create_config(desc, best)
     g.gemm_run(plan, Ad, Bd, Cd, bd)
     torch.cuda.synchronize()
@@ -655,3 +662,41 @@ def test_k_tail_every_length_on_every_mfma_tile(g):
             C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg))
             assert torch.equal(C[0].double(), A[0].double() @ B[0].double().T), (cfg, K)
         say(f"k tails {cfg}: ok")
+
+
+# ---- persistent workgroups -------------------------------------------------------------------
+
+def test_persistent_workgroups_exact(g, oracle):
+    """A persistent workgroup walks over several tiles as one stream of slabs: one, two and three
+    tiles per workgroup with a remainder, even and odd slab counts (the LDS stage a tile starts in
+    alternates), ragged edges, both output types, bias + activation, padded C rows, batches.
+    Integer data: bit exact against the oracle."""
+    for cfg in persistent_configs(g):
+        tile = 128 if "128x128" in cfg else 256
+        per_round = 512 if tile == 128 else 256            # workgroups the chip holds at once
+        for (tiles_m, tiles_n, K, batch) in [(2, 3, 128, 1), (17, 17, 192, 1), (24, 23, 128, 1), (3, 2, 320, 3),
+                                             (33, 20, 128, 1)]:
+            if tile == 256 and tiles_m * tiles_n > 300:
+                continue                                    # (keeps the oracle's share of the test short)
+            M, N = tiles_m * tile - 5, tiles_n * tile - 12
+            w = wl.Workload("t", M, N, K, batch=batch, epilogue="bias_relu", seed_a=31, seed_b=32, seed_bias=33)
+            say(f"persistent {cfg} {M}x{N}x{K} b{batch}: {tiles_m * tiles_n} tiles on {per_round} workgroups")
+            exact_case(g, oracle, w, cfg, lo=-2, hi=2)
+            exact_case(g, oracle, wl.scaled(w, epilogue="none"), cfg, out_dtype="f32", pad_c=4)
+
+
+def test_persistent_workgroups_random_and_misaligned_c(g, oracle):
+    """Random data against the oracle on the persistent configurations (several tiles per workgroup,
+    GELU epilogue), and a C whose rows are not 16-byte aligned: the plan must still be right (it
+    falls back to one tile per workgroup)."""
+    for cfg in persistent_configs(g):
+        tile = 128 if "128x128" in cfg else 256
+        n = 23 if tile == 128 else 17
+        w = wl.scaled(wl.WORKLOADS["gelu_8192x16384x4096"], M=n * tile - 3, N=n * tile, K=192)
+        A, B, bias = wl.make_inputs(w)
+        ref = run_oracle(oracle, w, A, B, bias)
+        say(f"persistent random {cfg} {w.M}x{w.N}x{w.K}")
+        C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg))
+        say("   ", assert_parity(w, C, ref, A, B, bias))
+        C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg), pad_c=3)     # ldc not a multiple of 8
+        assert_parity(w, C, ref, A, B, bias)
