@@ -32,9 +32,10 @@ def sources_newer_than_lib() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, only: tuple = ()) -> str:
     """Compile every kernel instantiation for gfx950 (one object per translation unit, side by
-    side) and link them into one shared library."""
+    side) and link them into one shared library.  `only`: source file names to recompile (the
+    other objects are taken as they are; for development, when a change touches one unit)."""
     from concurrent.futures import ThreadPoolExecutor
     os.makedirs(OBJ_DIR, exist_ok=True)
     flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -45,6 +46,8 @@ def build_library(verbose: bool = False) -> str:
 
     def compile_one(src):
         obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        if only and os.path.basename(src) not in only and os.path.exists(obj):
+            return src, obj, subprocess.CompletedProcess([], 0, "", "")
         res = subprocess.run([_hipcc()] + flags + ["-c", src, "-o", obj], capture_output=True, text=True)
         return src, obj, res
 
@@ -66,7 +69,8 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("kernels that keep data in scratch memory (the hand-scheduled kernels place their own "
                            "waits for asynchronous LDS reads and matrix-core results; a register the compiler "
                            "moves to memory in between breaks that):\n  " + "\n  ".join(bad))
-    res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs,
+    res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC",
+                          "-Wl,--version-script=" + os.path.join(CSRC, "exports.map"), "-o", LIB] + objs,
                          capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("linking failed:\n" + res.stderr)
