@@ -72,7 +72,8 @@ enum {
   GEMM_ERR_BAD_ENUM = -8,     /* an enum field holds a value outside its range */
   GEMM_ERR_BAD_CONFIG = -9,   /* tile configuration index unknown or not applicable */
   GEMM_ERR_BAD_SCALE = -10,   /* a *_SCALE epilogue with a scale that is not finite */
-  GEMM_ERR_WORKSPACE = -11    /* the plan needs a workspace (gemm_run_workspace), or the one given is too small / misaligned */
+  GEMM_ERR_WORKSPACE = -11,   /* the plan needs a workspace (gemm_run_workspace), or the one given is too small / misaligned */
+  GEMM_ERR_FIXED_SCRATCH = -12 /* gemm_run_fixed_scratch: the plan needs more than GEMM_FIXED_SCRATCH_BYTES of workspace */
 };
 
 /*
@@ -208,6 +209,28 @@ int gemm_create_splitk(const gemm_desc_t* desc, int splits, gemm_plan_t** out_pl
 size_t gemm_workspace_bytes(const gemm_plan_t* plan);
 int gemm_run_workspace(const gemm_plan_t* plan, const void* A, const void* B, void* C,
                        const void* bias, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * gemm_run_fixed_scratch - gemm_run_workspace for callers that cannot allocate device memory
+ * or pass a workspace along: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The split-K partial results go to a fixed buffer of
+ * GEMM_FIXED_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs
+ * on holds its own copy until the process ends); nothing is allocated or freed, here or in any
+ * call it makes.  A, B, C, bias and hip_stream as for gemm_run.
+ *   - A plan whose gemm_workspace_bytes exceeds GEMM_FIXED_SCRATCH_BYTES is refused with
+ *     GEMM_ERR_FIXED_SCRATCH and nothing is enqueued (use gemm_run_workspace).  Plans that need
+ *     no workspace run as with gemm_run.
+ *   - All calls on one GPU share that GPU's buffer, on every stream and for every plan: calls
+ *     whose work overlaps in time on one GPU race on it (the results of both are undefined).
+ *     Calls on one stream, or otherwise ordered, are safe: every partial result is written
+ *     before it is read, nothing carries over from one call to the next, nothing needs
+ *     clearing.
+ *   - The first call on a device looks up that device's copy of the buffer (no allocation);
+ *     GEMM_ERR_LAUNCH if the runtime cannot provide it.
+ */
+#define GEMM_FIXED_SCRATCH_BYTES ((size_t)32 << 20)
+int gemm_run_fixed_scratch(const gemm_plan_t* plan, const void* A, const void* B, void* C,
+                           const void* bias, void* hip_stream);
 
 /* gemm_destroy - release a plan.  NULL is a no-op that returns GEMM_OK. */
 int gemm_destroy(gemm_plan_t* plan);

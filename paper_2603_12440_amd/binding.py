@@ -130,6 +130,8 @@ def load_library():
     lib.gemm_workspace_bytes.argtypes = [ctypes.c_void_p]
     lib.gemm_run_workspace.restype = ctypes.c_int
     lib.gemm_run_workspace.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_size_t, ctypes.c_void_p]
+    lib.gemm_run_fixed_scratch.restype = ctypes.c_int
+    lib.gemm_run_fixed_scratch.argtypes = [ctypes.c_void_p] * 6
     lib.probe_mfma_peak.restype = ctypes.c_int
     lib.probe_mfma_peak.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double,
                                     ctypes.POINTER(ctypes.c_double)]
@@ -230,6 +232,19 @@ def gemm_run_workspace(plan: Plan, A, B, C, bias=None, workspace=None, workspace
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().gemm_run_workspace(plan.handle, _dev_ptr(A), _dev_ptr(B), _dev_ptr(C), _dev_ptr(bias),
                                              _dev_ptr(workspace), workspace_bytes, stream or None))
+
+
+FIXED_SCRATCH_BYTES = 32 << 20
+
+
+def gemm_run_fixed_scratch(plan: Plan, A, B, C, bias=None, stream: Optional[int] = None) -> None:
+    """As gemm_run_workspace, with the library's own fixed scratch buffer (no allocation anywhere;
+    plans that need more than FIXED_SCRATCH_BYTES are refused)."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(load_library().gemm_run_fixed_scratch(plan.handle, _dev_ptr(A), _dev_ptr(B), _dev_ptr(C),
+                                                 _dev_ptr(bias), stream or None))
 
 
 def gemm_tune(desc: GemmDesc, A, B, C, bias=None, stream: Optional[int] = None,

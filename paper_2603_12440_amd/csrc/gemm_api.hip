@@ -700,6 +700,48 @@ int gemm_run_workspace(const gemm_plan_t* plan, const void* A, const void* B, vo
   return hipGetLastError() == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }
 
+// ---- the fixed scratch buffer -----------------------------------------------------------------
+// Device memory inside the code object: each GPU the library is loaded on has its own copy at
+// its own address.  In host code the array's name is only a handle for hipGetSymbolAddress;
+// the address it returns (per device, looked up once with that device current) is what kernels
+// and launches are given.
+static __device__ __align__(256) unsigned char g_fixed_scratch[GEMM_FIXED_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of the buffer, or nullptr.
+void* fixed_scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_fixed_scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int gemm_run_fixed_scratch(const gemm_plan_t* plan, const void* A, const void* B, void* C,
+                           const void* bias, void* hip_stream) {
+  if (!plan) return GEMM_ERR_NULL;
+  if (!plan->inner) return gemm_run(plan, A, B, C, bias, hip_stream);
+  const size_t need = gemm_workspace_bytes(plan);
+  if (need > GEMM_FIXED_SCRATCH_BYTES) return GEMM_ERR_FIXED_SCRATCH;
+  int rc = check_device_gfx950();
+  if (rc != GEMM_OK) return rc;
+  void* ws = fixed_scratch_of_current_device();
+  if (!ws) return GEMM_ERR_LAUNCH;
+  return gemm_run_workspace(plan, A, B, C, bias, ws, GEMM_FIXED_SCRATCH_BYTES, hip_stream);
+}
+
 int gemm_create(const gemm_desc_t* desc, gemm_plan_t** out_plan) {
   return gemm_create_config(desc, -1, out_plan);
 }
@@ -946,6 +988,7 @@ const char* gemm_status_string(int status) {
     case GEMM_ERR_BAD_CONFIG: return "tile configuration unknown or not applicable";
     case GEMM_ERR_BAD_SCALE: return "epilogue scale is not finite";
     case GEMM_ERR_WORKSPACE: return "plan needs a workspace (gemm_run_workspace), or the workspace is too small or misaligned";
+    case GEMM_ERR_FIXED_SCRATCH: return "plan needs more workspace than the library's fixed scratch buffer of 32 MiB (use gemm_run_workspace)";
     default: return "unknown status";
   }
 }
