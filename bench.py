@@ -9,10 +9,15 @@ the throughput (TFLOP/s for matrix-core-bound shapes, GB/s for HBM-bound ones),
 the roofline fraction of the kernel measured with HIP events on the launch
 stream, and the CPU oracle timed on a bounded sample of the same workload.
 
-The timing loop follows the paper's protocol in spirit (App. "Benchmarking
-kernel runtime"): untimed warm-up, many launches between two synchronisations,
-and no result is cached or reused between launches (HBM-bound shapes rotate
-through several weight buffers so that the last-level cache cannot serve them).
+The timing follows the paper's protocol (App. "Benchmarking kernel runtime"):
+an untimed warm-up of at least --warmup launches, one second and ten launches,
+then exactly --steps launches between two synchronisations (median / min / p10 /
+p90 of single launches come from a following pass with an event per launch), and
+no result is cached or reused between launches (HBM-bound
+shapes rotate through several weight buffers so that the last-level cache cannot
+serve them).  Shader clock and board power are sampled from sysfs while the
+warm-up and the timed launches run.  The default line also carries a `secondary`
+entry: the decode-shaped GEMV (M = 1, N = K = 8192) measured the same way.
 """
 from __future__ import annotations
 
@@ -49,6 +54,8 @@ def parse():
     ap.add_argument("--tune", action="store_true",
                     help="pick the tile configuration with gemm_tune (times every applicable one first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the second headline shape (M = 1, N = K = 8192) that the default line also carries")
     ap.add_argument("--no-measured-peak", action="store_true",
                     help="skip the MFMA-only / streaming-read probe that the roofline fraction is also related to")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -127,7 +134,7 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
         sub = wl.scaled(w, M=rows, batch=1)
         p = oracle_problem(oracle, sub)
         t0 = time.perf_counter()
-        oracle.ref_gemm(p, a, b, bz, want=("y",))
+        run.last = oracle.ref_gemm(p, a, b, bz, want=("y",))
         return time.perf_counter() - t0
 
     cores = oracle.num_threads()
@@ -137,6 +144,20 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
     rows = int(min(w.M, max(r0, target_s / per_row)))
     rows = max(cores, rows - rows % cores) if rows >= cores else rows
     t = run(rows)
+    # every element of the rows just computed against the GPU's: the same bound with S replaced by
+    # its Cauchy-Schwarz majorant |a_i| |b_j| (the timed call returns y only)
+    if w.epilogue == "none":
+        af = wl.to_float64(A[0, :rows] if w.layout_a == "row" else A[0, :, :rows].T)
+        bf = wl.to_float64(B[0] if w.layout_b == "col" else B[0].T)
+        na, nb = np.sqrt((af * af).sum(axis=1)), np.sqrt((bf * bf).sum(axis=1))
+        yr = run.last["y"].reshape(rows, w.N)
+        gr = gpu_out[0, :rows].to(torch.float64).numpy()
+        accr = 1.13 * w.K * 2.0 ** -24 * np.outer(na, nb)
+        rows_ok = bool(np.all(np.abs(gr - yr) <= accr + u_out * (np.abs(yr) + accr) * 1.001 + 1e-30))
+        matches = matches and rows_ok
+        rows_note = f"; all {rows} x {w.N} of these outputs compared with the GPU's: {'ok' if rows_ok else 'MISMATCH'}"
+    else:
+        rows_note = ""
     flops = 2.0 * rows * w.N * w.K
     if w.bound == "hbm":
         e = 2 if w.dtype != "f32" else 4
@@ -146,7 +167,7 @@ def cpu_baseline(w, A, B, bias, target_s, gpu_out):
     return {"value": val, "unit": unit, "cores": cores, "kind": "oracle",
             "gpu_output_matches_oracle_samples": matches,
             "sample": f"first {rows} of {w.M} output rows x all {w.N} columns, full K={w.K}, "
-                      f"batch 0, fp64 triple loop, {t:.2f} s wall"}
+                      f"batch 0, fp64 triple loop, {t:.2f} s wall" + rows_note}
 
 
 def measured_peak(g, dev, bound, dtype):
@@ -180,6 +201,128 @@ def copy_calibration(dev):
     del src, dst
 
 
+class Telemetry:
+    """Samples the shader clock (the starred level of pp_dpm_sclk) and the board power (hwmon
+    power1_input, microwatts) of card0 from sysfs in a background thread."""
+
+    def __init__(self, period=0.01):
+        import glob
+        self.period = period
+        self.sclk_path = next(iter(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")), None)
+        self.power_path = next(iter(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")), None) or \
+            next(iter(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")), None)
+        self.sclk, self.power = [], []
+        self._stop = False
+        self._thread = None
+
+    def _read(self):
+        try:
+            if self.sclk_path:
+                for line in open(self.sclk_path):
+                    if "*" in line:
+                        self.sclk.append(float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip()))
+            if self.power_path:
+                self.power.append(float(open(self.power_path).read()) * 1e-6)
+        except (OSError, ValueError, IndexError):
+            pass
+
+    def __enter__(self):
+        import threading
+
+        def loop():
+            while not self._stop:
+                self._read()
+                time.sleep(self.period)
+        self._thread = threading.Thread(target=loop, daemon=True)
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        self._thread.join()
+
+    def summary(self):
+        def med(v):
+            return round(float(np.median(v)), 1) if v else None
+        return {"sclk_mhz_median": med(self.sclk), "sclk_mhz_min": round(min(self.sclk), 1) if self.sclk else None,
+                "power_w_median": med(self.power), "power_w_max": round(max(self.power), 1) if self.power else None,
+                "samples": max(len(self.sclk), len(self.power)),
+                "what": "sysfs pp_dpm_sclk / hwmon power1, sampled while the warm-up and the timed launches ran"}
+
+
+def timed_launches(step, steps, warmup, min_warm_seconds=1.0, min_warm_launches=10):
+    """The paper's protocol around `step(i)`: untimed warm-up (at least `warmup` launches, and until
+    `min_warm_seconds` and `min_warm_launches` have passed), then exactly `steps` launches between two
+    synchronisations (one event before, one after).  Returns (wall ms per step, mean kernel ms per step
+    from the two events, per-launch statistics from a following pass, launches of the warm-up)."""
+    n = 0
+    t0 = time.perf_counter()
+    while n < warmup or n < min_warm_launches or time.perf_counter() - t0 < min_warm_seconds:
+        for _ in range(8):
+            step(n)
+            n += 1
+        torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        step(n + i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = ev0.elapsed_time(ev1) / steps
+    # the spread of single launches, in a pass of its own (an event between launches costs a
+    # microsecond or two of idle time each, which the mean above should not carry)
+    m = min(steps, 200)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(m + 1)]
+    ev[0].record()
+    for i in range(m):
+        step(n + steps + i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(m)])
+    stats = {"median_ms": round(float(np.median(per)), 6), "min_ms": round(float(per.min()), 6),
+             "p10_ms": round(float(np.percentile(per, 10)), 6), "p90_ms": round(float(np.percentile(per, 90)), 6),
+             "launches": m,
+             "what": "durations between consecutive events, one event per launch, in a pass after the timed region"}
+    return wall * 1e3 / steps, kern_ms, stats, n
+
+
+def bench_secondary(g, dev, name="skinny_m1_n8192", steps=400):
+    """The second headline shape, measured like the first: the decode-shaped GEMV with rotated weight
+    buffers, its roofline fraction, and every output checked against the oracle."""
+    w = wl.WORKLOADS[name]
+    A, B, bias = wl.make_inputs(w)
+    plan = g.gemm_create(gpu_desc(g, w))
+    nbuf = min(64, max(2, int(np.ceil(1.2e9 / w.bytes))))
+    Ad = [A.to(dev) for _ in range(nbuf)]
+    Bd = [B.to(dev) for _ in range(nbuf)]
+    Cd = [torch.empty((w.batch, w.M, w.N), dtype=wl.TORCH_DTYPE[w.out_dtype or w.dtype], device=dev) for _ in range(nbuf)]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(i):
+        j = i % nbuf
+        g.gemm_run(plan, Ad[j], Bd[j], Cd[j], None, stream)
+    ms_wall, ms_kern, stats, _ = timed_launches(step, steps, 20, min_warm_seconds=0.3)
+    info = plan.info()
+    g.gemm_destroy(plan)
+    achieved = w.bytes / (ms_kern * 1e-3) / 1e9
+    import oracle
+    oracle.build()
+    p = oracle.Problem(w.M, w.N, w.K, oracle.DTYPE_BF16, oracle.DTYPE_BF16, oracle.ROW_MAJOR, oracle.COL_MAJOR)
+    ref = oracle.ref_gemm(p, wl.storage_numpy(A), wl.storage_numpy(B), None, want=("y", "s"))
+    got = Cd[0].to(torch.float64).cpu().numpy().reshape(ref["y"].shape)
+    acc = w.K * 2.0 ** -24 * ref["s"]
+    ok = bool(np.all(np.abs(got - ref["y"]) <= acc + 2.0 ** -8 * (np.abs(ref["y"]) + acc) * 1.001 + 1e-30))
+    return {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "metric": "HBM-bound GEMM throughput (algorithmic bytes / time)",
+            "value": round(w.bytes / (ms_wall * 1e-3) / 1e9, 3), "unit": "GB/s", "steps": steps,
+            "ms_per_step": round(ms_wall, 6), "per_launch": stats, "plan": info, "buffers_rotated": nbuf,
+            "roofline": {"bound": "hbm", "achieved": round(achieved, 3), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": measured_traffic(w.name)},
+            "gpu_output_matches_oracle": ok, "oracle_check": f"all {w.M * w.N} outputs, fp64 oracle, a-priori bound"}, ok
+
+
 def bench_rope(args, g, dev):
     """A rotary-embedding workload: one step = the query and the key tensor of a layer rotated in
     one launch (include/rope.h).  HBM-bound: algorithmic bytes = every element read and written once."""
@@ -204,19 +347,9 @@ def bench_rope(args, g, dev):
     if args.copy_calibration:
         copy_calibration(dev)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for i in range(args.steps):
-        step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    with Telemetry() as tel:
+        ms_per_step, kern_ms, per_launch, warm_launches = timed_launches(step, args.steps, args.warmup)
+    last_step = warm_launches + args.steps - 1
     achieved = w.bytes / (kern_ms * 1e-3) / 1e9
     out = {
         "metric": "rotary embedding throughput (algorithmic bytes / time)",
@@ -224,6 +357,7 @@ def bench_rope(args, g, dev):
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
+        "per_launch": per_launch, "warmup_launches_run": warm_launches, "telemetry": tel.summary(),
         "config": {"workload": w.name, "batch": w.batch, "heads_q": w.heads_q, "heads_k": w.heads_k,
                    "seq": w.seq, "head_dim": w.head_dim, "storage": w.dtype, "tables": w.table_dtype,
                    "layout": "[batch, seq, heads, head_dim] memory, rotated as [batch, heads, seq, head_dim]",
@@ -261,7 +395,7 @@ def bench_rope(args, g, dev):
                 P = int(max(P, min(w.seq, P * args.cpu_seconds / max(t, 1e-6))))
                 continue
             break
-        j = (args.steps - 1) % nbuf
+        j = last_step % nbuf
         u = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24}[w.dtype]
         for ref, y in zip(refs, (qy[j], ky[j])):
             got = wl.to_float64(y[:, :P].cpu().transpose(1, 2))
@@ -295,9 +429,11 @@ def main():
     desc = gpu_desc(g, w)
     cfg = -1 if args.config is None else g.config_names().index(args.config)
     if args.tune:
-        odt0 = wl.TORCH_DTYPE[w.dtype]
-        cfg, _ = g.gemm_tune(desc, A.to(dev), B.to(dev), torch.empty((w.batch, w.M, w.N), dtype=odt0, device=dev),
-                             None if bias is None else bias.to(dev), min_seconds=0.2)
+        odt0 = wl.TORCH_DTYPE[w.out_dtype or w.dtype]            # the descriptor's dtype_c: every candidate writes that
+        c_tune = torch.empty((w.batch, w.M, w.N), dtype=odt0, device=dev)
+        assert c_tune.numel() * c_tune.element_size() == w.batch * w.M * w.N * {"f32": 4, "bf16": 2, "f16": 2}[w.out_dtype or w.dtype]
+        cfg, _ = g.gemm_tune(desc, A.to(dev), B.to(dev), c_tune, None if bias is None else bias.to(dev), min_seconds=0.2)
+        del c_tune
     plan = g.gemm_create_config(desc, cfg) if args.splitk is None else g.gemm_create_splitk(desc, args.splitk)
     info = plan.info()
     ws_bytes = g.gemm_workspace_bytes(plan)
@@ -326,19 +462,9 @@ def main():
     if args.copy_calibration:
         copy_calibration(dev)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for i in range(args.steps):
-        step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    kern_ms = ev0.elapsed_time(ev1) / args.steps       # average launch duration on the launch stream
+    with Telemetry() as tel:
+        ms_per_step, kern_ms, per_launch, warm_launches = timed_launches(step, args.steps, args.warmup)
+    last_step = warm_launches + args.steps - 1           # (the buffers rotate with the launch count)
 
     if w.bound == "hbm":
         metric, unit = "HBM-bound GEMM throughput (algorithmic bytes / time)", "GB/s"
@@ -355,6 +481,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
+        "per_launch": per_launch, "warmup_launches_run": warm_launches, "telemetry": tel.summary(),
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "batch": w.batch,
                    "layout": f"A {w.layout_a}-major, B {w.layout_b}-major, C row-major",
                    "epilogue": w.epilogue, "plan": info, "buffers_rotated": nbuf},
@@ -369,10 +496,15 @@ def main():
     ok = True
     if not args.no_cpu_baseline:
         # the paper's "no result reuse" rule: the last timed launch's output is checked
-        last = Cd[(args.steps - 1) % nbuf].cpu()
+        last = Cd[last_step % nbuf].cpu()
         out["cpu_baseline"] = cpu_baseline(w, A, B, bias, args.cpu_seconds, last)
         ok = out["cpu_baseline"]["gpu_output_matches_oracle_samples"]
     g.gemm_destroy(plan)
+    if args.workload == "square_8192" and not args.no_secondary and not args.copy_calibration:
+        del Ad, Bd, Cd
+        sec, sec_ok = bench_secondary(g, dev)
+        out["secondary"] = [sec]
+        ok = ok and sec_ok
     print(json.dumps(out))
     return 0 if ok else 1
 

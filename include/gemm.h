@@ -235,6 +235,12 @@ int gemm_run_fixed_scratch(const gemm_plan_t* plan, const void* A, const void* B
 /* gemm_destroy - release a plan.  NULL is a no-op that returns GEMM_OK. */
 int gemm_destroy(gemm_plan_t* plan);
 
+/*
+ * Logging (the paper's profiler feedback reports which kernel variant ran, App. "Profiler
+ * Feedback"): with GEMM_LOG=1 in the environment every gemm_create* writes one line to stderr
+ * with the problem and the text gemm_plan_info gives for the plan it made.
+ */
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* gemm_status_string(int status);
 

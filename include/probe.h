@@ -4,7 +4,7 @@
  * nominal figures (2516.6 TFLOP/s bf16, 8 TB/s) assume the nominal clock; under sustained
  * matrix-core load the chip clocks lower, and a kernel's distance from what the hardware
  * actually delivers is the more useful number next to its roofline fraction (the paper's
- * profiler feedback, Sec. 3.3, reports "X-bound at Y % of peak" the same way).
+ * profiler feedback, Sec. 3.3, likewise names the bounding resource and the share of its peak).
  * Measurement helpers only: nothing in the GEMM or rotary paths calls them.
  *
  * Both calls enqueue on `hip_stream` (NULL = default stream), WAIT for the device, create

@@ -3,11 +3,10 @@
  * shared library as the GEMM entry points (include/gemm.h; its dtype enum and status
  * codes are used here).
  *
- * The operation is the one of the paper's language-model case study (Sec. 4, "Case
- * study": the rotary embedding function of a Llama-style model, reference = the PyTorch
- * "apply_rotary_pos_emb, combining unsqueeze + rotate-half").  For every head vector x
- * (even length D) at position s of batch b, with per-position tables cos, sin of length D
- * that are shared by all heads (the "unsqueeze"):
+ * The operation is the rotary embedding of the paper's language-model case study (Sec. 4,
+ * case study on a Llama-style model): the rotate-half form, with per-position tables that
+ * are broadcast over the heads.  For every head vector x (even length D) at position s of
+ * batch b, with per-position tables cos, sin of length D that are shared by all heads:
  *
  *     rot(x)[i] = -x[i + D/2]  (i < D/2),    rot(x)[i] = x[i - D/2]  (i >= D/2)
  *     y[i]      = x[i] * cos[i] + rot(x)[i] * sin[i]

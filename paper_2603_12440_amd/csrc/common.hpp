@@ -1,7 +1,7 @@
 // Shared device-side helpers for the gfx950 GEMM kernels: storage types,
 // conversions and the fused epilogue (bias + activation, computed in fp32 on
-// the accumulators; Sec. 3.2 of the paper files this under "fused operations,
-// single pass over data").
+// the accumulators: in the taxonomy of Sec. 3.2 of the paper, operator fusion with one
+// pass over the data).
 #pragma once
 
 #include <hip/hip_runtime.h>

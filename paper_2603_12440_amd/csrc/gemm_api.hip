@@ -109,9 +109,8 @@ hipError_t launch_simt(const gemm_plan& pl, const void* A, const void* B, void* 
   return launch_simt_typed<TIn, TIn, TM, TN, TK>(pl, A, B, C, bias, s);
 }
 
-template <typename T, int MB, int WAVES>
-hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void* C,
-                         const void* bias, hipStream_t s) {
+// the argument block every skinny kernel takes
+SkinnyArgs skinny_args(const gemm_plan& pl, const void* A, const void* B, void* C, const void* bias) {
   const gemm_desc_t& d = pl.d;
   SkinnyArgs a;
   a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
@@ -123,61 +122,34 @@ hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void
   a.act = epilogue_activation(d.epilogue);
   a.scale = d.scale;
   a.y_f32 = d.dtype_c == GEMM_F32;
-  skinny_gemm_kernel<T, MB, WAVES><<<pl.grid, pl.block, 0, s>>>(a);
+  return a;
+}
+
+template <typename T, int MB, int WAVES>
+hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void* C,
+                         const void* bias, hipStream_t s) {
+  skinny_gemm_kernel<T, MB, WAVES><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
   return hipGetLastError();
 }
 
 template <typename T, int RB, int UNROLL>
 hipError_t launch_skinny_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
                               const void* bias, hipStream_t s) {
-  const gemm_desc_t& d = pl.d;
-  SkinnyArgs a;
-  a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
-  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
-  a.ldx = d.lda; a.ldw = d.ldb; a.ldy = d.ldc;
-  a.stride_x = d.stride_a; a.stride_w = d.stride_b; a.stride_y = d.stride_c;
-  a.stride_bias = d.stride_bias;
-  a.has_bias = epilogue_has_bias(d.epilogue);
-  a.act = epilogue_activation(d.epilogue);
-  a.scale = d.scale;
-  a.y_f32 = d.dtype_c == GEMM_F32;
-  skinny_mfma_kernel<T, RB, UNROLL><<<pl.grid, pl.block, 0, s>>>(a);
+  skinny_mfma_kernel<T, RB, UNROLL><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
   return hipGetLastError();
 }
 
 template <typename T, int NS>
 hipError_t launch_skinny_ring(const gemm_plan& pl, const void* A, const void* B, void* C,
                               const void* bias, hipStream_t s) {
-  const gemm_desc_t& d = pl.d;
-  SkinnyArgs a;
-  a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
-  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
-  a.ldx = d.lda; a.ldw = d.ldb; a.ldy = d.ldc;
-  a.stride_x = d.stride_a; a.stride_w = d.stride_b; a.stride_y = d.stride_c;
-  a.stride_bias = d.stride_bias;
-  a.has_bias = epilogue_has_bias(d.epilogue);
-  a.act = epilogue_activation(d.epilogue);
-  a.scale = d.scale;
-  a.y_f32 = d.dtype_c == GEMM_F32;
-  skinny_ring_kernel<T, NS><<<pl.grid, pl.block, 0, s>>>(a);
+  skinny_ring_kernel<T, NS><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
   return hipGetLastError();
 }
 
 template <typename T, int DEPTH, int RB, int WAVES>
 hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B, void* C,
                                const void* bias, hipStream_t s) {
-  const gemm_desc_t& d = pl.d;
-  SkinnyArgs a;
-  a.X = A; a.W = B; a.Y = C; a.bias = (const float*)bias;
-  a.M = (int)d.M; a.N = (int)d.N; a.K = (int)d.K;
-  a.ldx = d.lda; a.ldw = d.ldb; a.ldy = d.ldc;
-  a.stride_x = d.stride_a; a.stride_w = d.stride_b; a.stride_y = d.stride_c;
-  a.stride_bias = d.stride_bias;
-  a.has_bias = epilogue_has_bias(d.epilogue);
-  a.act = epilogue_activation(d.epilogue);
-  a.scale = d.scale;
-  a.y_f32 = d.dtype_c == GEMM_F32;
-  skinny_stage_kernel<T, DEPTH, RB, WAVES><<<pl.grid, pl.block, 0, s>>>(a);
+  skinny_stage_kernel<T, DEPTH, RB, WAVES><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
   return hipGetLastError();
 }
 
@@ -287,7 +259,20 @@ const Config kConfigs[] = {
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
-constexpr int kNumCUs = 256;   // MI355X
+// Compute units of the device the plans are made for: asked of the runtime once (the current
+// device at the first plan); 256, an MI355X, where no device can be asked (plans can be made
+// and inspected on a machine without a GPU).
+int num_cus() {
+  static const int n = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      return cus;
+    (void)hipGetLastError();
+    return 256;
+  }();
+  return n;
+}
 
 // ---- validation -----------------------------------------------------------------------
 
@@ -324,12 +309,19 @@ int resolve(const gemm_desc_t* in, gemm_desc_t* out) {
   if (d.lda < a_minor || d.ldb < b_minor || d.ldc < c_minor) return GEMM_ERR_BAD_LD;
   const int64_t kMaxLd = (int64_t)1 << 40;
   if (d.lda > kMaxLd || d.ldb > kMaxLd || d.ldc > kMaxLd) return GEMM_ERR_BAD_LD;
-  const int64_t a_span = (a_major - 1) * d.lda + a_minor;
-  const int64_t b_span = (b_major - 1) * d.ldb + b_minor;
-  const int64_t c_span = (c_major - 1) * d.ldc + c_minor;
-  if (d.stride_a == 0) d.stride_a = a_major * d.lda;
-  if (d.stride_b == 0) d.stride_b = b_major * d.ldb;
-  if (d.stride_c == 0) d.stride_c = c_major * d.ldc;
+  // extents in elements: major * ld must stay below 2^62 (no signed overflow anywhere below)
+  int64_t a_full, b_full, c_full;
+  const int64_t kMaxSpan = (int64_t)1 << 62;
+  if (__builtin_mul_overflow(a_major, d.lda, &a_full) || a_full >= kMaxSpan ||
+      __builtin_mul_overflow(b_major, d.ldb, &b_full) || b_full >= kMaxSpan ||
+      __builtin_mul_overflow(c_major, d.ldc, &c_full) || c_full >= kMaxSpan)
+    return GEMM_ERR_BAD_LD;
+  const int64_t a_span = a_full - d.lda + a_minor;
+  const int64_t b_span = b_full - d.ldb + b_minor;
+  const int64_t c_span = c_full - d.ldc + c_minor;
+  if (d.stride_a == 0) d.stride_a = a_full;
+  if (d.stride_b == 0) d.stride_b = b_full;
+  if (d.stride_c == 0) d.stride_c = c_full;
   if (d.batch > 1) {
     // Reading one A or B slab for several batches would be legal, but the stride
     // field uses 0 for "packed", so overlapping inputs are not expressible; an
@@ -393,9 +385,9 @@ double mfma_cost(const Config& c, int64_t M, int64_t N, int64_t K, int64_t batch
   // (8192^3: 732 against 800 us); of the two 256x256 shapes the eight-wave one goes first
   if (!std::strncmp(c.name, "mfma16_", 7)) eff *= c.threads == 256 && area >= 256 * 256 ? 1.08 : 1.10;
   const double tiles = (double)((M + c.bm - 1) / c.bm) * (double)((N + c.bn - 1) / c.bn) * (double)batch;
-  const double rounds = (double)(int64_t)((tiles + kNumCUs * per_cu - 1) / (kNumCUs * per_cu));
+  const double rounds = (double)(int64_t)((tiles + num_cus() * per_cu - 1) / (num_cus() * per_cu));
   // workgroups that actually share a CU (a lone workgroup runs about per_cu times faster)
-  const double sharing = tiles >= (double)kNumCUs * per_cu ? per_cu : (tiles > kNumCUs ? tiles / kNumCUs : 1.0);
+  const double sharing = tiles >= (double)num_cus() * per_cu ? per_cu : (tiles > num_cus() ? tiles / num_cus() : 1.0);
   return rounds * area * sharing / eff * ((double)K + 600.0);
 }
 
@@ -421,8 +413,8 @@ int64_t split_columns(const gemm_desc_t& d, int big, double single_cost) {
   const Config& c = kConfigs[big];
   if (c.bm != 256 || c.bn != 256) return 0;
   const int64_t tiles_m = (d.M + c.bm - 1) / c.bm, tiles_n = (d.N + c.bn - 1) / c.bn;
-  if (tiles_m > kNumCUs || kNumCUs % tiles_m != 0) return 0;
-  const int64_t cols_per_round = kNumCUs / tiles_m;
+  if (tiles_m > num_cus() || num_cus() % tiles_m != 0) return 0;
+  const int64_t cols_per_round = num_cus() / tiles_m;
   const int64_t cols_big = tiles_n / cols_per_round * cols_per_round;
   if (cols_big == 0 || cols_big == tiles_n) return 0;
   const int64_t n_first = cols_big * c.bn;
@@ -445,7 +437,7 @@ int choose(const gemm_desc_t& d) {
   if (d.M > 4 && d.M <= 16) {
     // register-staged MFMA kernel: the long-burst variant when there is at most one
     // workgroup per CU anyway, the lighter one (several workgroups per CU) otherwise
-    const bool one_round = (d.N + 31) / 32 <= kNumCUs;
+    const bool one_round = (d.N + 31) / 32 <= num_cus();
     const int i = find_config(one_round ? "skinnystage_d2_b512" : "skinnystage_d3_b256");
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
@@ -473,8 +465,8 @@ int choose(const gemm_desc_t& d) {
   // against 2.00 ms).
   const double tiles32 = (double)((d.M + 31) / 32) * (double)((d.N + 31) / 32) * d.batch;
   const double tiles128 = (double)((d.M + 127) / 128) * (double)((d.N + 127) / 128) * d.batch;
-  if (tiles32 <= 2.0 * kNumCUs) return find_config("simt_32x32x64");
-  return find_config(tiles128 >= 4.0 * kNumCUs ? "general_mfma32_128x128x16" : "general_mfma32_64x64x16");
+  if (tiles32 <= 2.0 * num_cus()) return find_config("simt_32x32x64");
+  return find_config(tiles128 >= 4.0 * num_cus() ? "general_mfma32_128x128x16" : "general_mfma32_64x64x16");
 }
 
 int fill_launch_shape(gemm_plan& pl) {
@@ -491,7 +483,7 @@ int fill_launch_shape(gemm_plan& pl) {
     const int64_t tm = (d.M + c.bm - 1) / c.bm, tn = (d.N + c.bn - 1) / c.bn;
     int64_t wgs = tm * tn;
     if (c.persist) {                           // as many workgroups as run at once; each takes every wgs-th tile
-      const int64_t at_once = (int64_t)kNumCUs * (160 * 1024 / c.lds_bytes);
+      const int64_t at_once = (int64_t)num_cus() * (160 * 1024 / c.lds_bytes);
       if (wgs > at_once) wgs = at_once;
     }
     pl.grid = dim3((unsigned)wgs, (unsigned)d.batch, 1);
@@ -501,14 +493,14 @@ int fill_launch_shape(gemm_plan& pl) {
     pl.grid = dim3((unsigned)((d.N + c.bn - 1) / c.bn), (unsigned)d.batch, 1);
   } else if (c.kind == KIND_SKINNY_MFMA) {
     const int64_t blocks = (d.N + c.bn - 1) / c.bn;
-    const int64_t want = (int64_t)kNumCUs * 2;
+    const int64_t want = (int64_t)num_cus() * 2;
     pl.grid = dim3((unsigned)(blocks < want ? blocks : want), (unsigned)d.batch, 1);
   } else {
     // One row of W per wave at a time, rows dealt round-robin: bn workgroups per CU,
     // more only if a wave would otherwise own more rows than the kernel has slots for.
     const int waves = c.threads / 64;
     int64_t wgs = (d.N + waves - 1) / waves;                       // one row per wave
-    const int64_t want = (int64_t)kNumCUs * c.bn;
+    const int64_t want = (int64_t)num_cus() * c.bn;
     if (wgs > want) wgs = want;
     const int64_t need = (d.N + (int64_t)waves * kSkinnyMaxRows - 1) / ((int64_t)waves * kSkinnyMaxRows);
     if (wgs < need) wgs = need;
@@ -523,6 +515,15 @@ int fill_launch_shape(gemm_plan& pl) {
 // ---- C ABI -------------------------------------------------------------------------------
 
 extern "C" {
+
+// GEMM_LOG=1 in the environment: one line on stderr per plan, saying which kernel and tile it got.
+static bool log_enabled() {
+  static const bool on = [] {
+    const char* e = std::getenv("GEMM_LOG");
+    return e && e[0] && std::strcmp(e, "0") != 0;
+  }();
+  return on;
+}
 
 int gemm_config_count(void) { return kNumConfigs; }
 
@@ -581,6 +582,12 @@ static int create_resolved(const gemm_desc_t& d, int config, bool allow_two_laun
   const int rc = fill_launch_shape(*pl);
   if (rc != GEMM_OK) { gemm_destroy(pl); return rc; }
   *out_plan = pl;
+  if (allow_two_launches && log_enabled()) {     // (second launches and split-K inner plans are reported with their parent)
+    char buf[512];
+    gemm_plan_info(pl, buf, sizeof(buf));
+    std::fprintf(stderr, "[mi355gemm] plan %lld x %lld x %lld batch %d dtype %d -> %d epilogue %d: %s\n", (long long)d.M,
+                 (long long)d.N, (long long)d.K, (int)d.batch, (int)d.dtype_a, (int)d.dtype_c, (int)d.epilogue, buf);
+  }
   return GEMM_OK;
 }
 

@@ -507,12 +507,14 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   const int elane = fresh_lane();
   const int er = elane & 31, eh = elane >> 5;
 
-  // bias of the 4 columns j .. j+3 (zero past N)
+  // bias of the 4 columns j .. j+3 (zero past N; j is a multiple of 4); 16-byte loads only when
+  // the bias vector of this batch starts at a 16-byte aligned address (the same for every lane)
+  const bool bias_vec = (((uintptr_t)bias) & 15) == 0;
   auto bias4 = [&](int j, float (&bv)[4]) __attribute__((always_inline)) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) bv[e] = 0.0f;
     if (!bias) return;
-    if (j + 3 < p.N) {
+    if (j + 3 < p.N && bias_vec) {
       const f32x4_t b4 = *(const f32x4_t*)(bias + j);
 #pragma unroll
       for (int e = 0; e < 4; ++e) bv[e] = b4[e];

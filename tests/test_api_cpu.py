@@ -304,3 +304,29 @@ def test_tuning_mode_switch_and_environment(g):
     assert run("1") == ["1", "1", "0", "0"]
     g.gemm_autotune_clear()
     assert g.gemm_autotune_entries() == 0
+
+
+def test_overflowing_extents_are_refused(g):
+    """major x ld beyond 2^62 elements cannot be addressed: BAD_LD, decided without overflow."""
+    for kw in (dict(M=1 << 30, N=64, K=64, lda=1 << 40), dict(M=64, N=1 << 30, K=64, ldb=1 << 40),
+               dict(M=1 << 30, N=64, K=64, ldc=1 << 40)):
+        with pytest.raises(g.GemmError) as e:
+            g.gemm_create(g.GemmDesc(**kw))
+        assert e.value.status == -3, kw
+
+
+def test_gemm_log_names_the_kernel():
+    """GEMM_LOG=1: one line per plan on stderr with the kernel and tile it got."""
+    import subprocess
+    import sys
+    code = ("import paper_2603_12440_amd as g; p = g.gemm_create(g.GemmDesc(8192, 8192, 8192)); g.gemm_destroy(p); "
+            "p = g.gemm_create(g.GemmDesc(1, 8192, 8192)); g.gemm_destroy(p)")
+    for env_val, want in (("1", 2), ("0", 0)):
+        r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT,
+                           env=dict(os.environ, GEMM_LOG=env_val))
+        assert r.returncode == 0, r.stderr
+        lines = [l for l in r.stderr.splitlines() if l.startswith("[mi355gemm] plan")]
+        assert len(lines) == want, r.stderr
+        if want:
+            assert "8192 x 8192 x 8192" in lines[0] and "kernel=mfma16_256x256" in lines[0]
+            assert "kernel=skinny_m1" in lines[1]
