@@ -221,7 +221,6 @@ const Config kConfigs[] = {
     SIMT_CFG(32, 32, 16),
     SIMT_CFG(32, 32, 64),
     MFMA16P_CFG(256, 256, 2, 4, 2),
-    MFMA16P_CFG(256, 256, 2, 2, 2),
     MFMA16P_CFG(128, 128, 2, 2, 2),
     MFMA16_CFG(256, 256, 2, 4, 2),
     MFMA16_CFG(256, 256, 2, 2, 2),

@@ -406,86 +406,154 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     constexpr int kShare = Cfg::LDS_BYTES / Cfg::kWaves;
     static_assert(16 * OROWB32 <= kShare, "one 16-row band of the wave block in fp32 must fit the wave's share of LDS");
     static_assert(OROWB == 128 || OROWB == 256, "staging rows of 128 or 256 bytes");
+    static_assert(2 * 16 * OROWB <= (PERSIST ? Cfg::EPI_BYTES / Cfg::kWaves : kShare), "two 16-bit bands per wave");
     // staging: this wave's share of the idle slab stages, or of the separate area of a persistent workgroup
     unsigned char* wt = PERSIST ? smem + Cfg::LDS_BYTES + wave * (Cfg::EPI_BYTES / Cfg::kWaves) : smem + wave * kShare;
     // chunk-slot key of staging row r: 128-byte rows alternate between the two halves of the banks,
     // longer rows all start at bank 0
     auto osw = [](int r) __attribute__((always_inline)) { return OROWB == 128 ? ((r >> 1) & 7) : (r & 15); };
 
-    // 16-bit through LDS, band m
-    auto drain16 = [&](auto actf, auto m_c) __attribute__((always_inline)) {
-      constexpr int m = decltype(m_c)::value;
-#pragma unroll
-      for (int n = 0; n < NT; ++n) {
-        const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
-        float bv[4];
-        bias4(j, bv);
-        float v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][e] + bv[e]);
-        const int q = n * 2 + (eq >> 1);
-        u32x2_t w = {pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
-        *(u32x2_t*)(wt + er * OROWB + ((q ^ osw(er)) * 16) + (eq & 1) * 8) = w;
-      }
+    // 16-bit through LDS, pipelined over the 16-row bands of the wave block with two staging
+    // buffers: while the rows of band m-1 come back from LDS, the values of band m+1 are computed;
+    // a band's stores are on their way to memory while the next one is drained.
+    constexpr int kBand16 = 16 * OROWB;             // bytes of one staged band
+    constexpr int kIt16 = 16 * CH / 64;             // wave-wide 16-byte accesses per band
+    auto drain16_all = [&](auto actf) __attribute__((always_inline)) {
       TO* Cb = (TO*)pe.C + batch * pe.stride_c;
       const int slane = fresh_lane();
+      u32x2_t w[NT];
+      u32x4_t val[kIt16];
+      float bvs[NT][4];                           // the bias of this lane's columns, the same for every band
 #pragma unroll
-      for (int it = 0; it < 16 * CH / 64; ++it) {
+      for (int n = 0; n < NT; ++n) bias4(col0 + wn * Cfg::WTN + n * 16 + eq * 4, bvs[n]);
+      auto values = [&](auto m_c) __attribute__((always_inline)) {
+        constexpr int m = decltype(m_c)::value;
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = actf(acc[m][n][e] + bvs[n][e]);
+          w[n] = u32x2_t{pack2<TO>(v[0], v[1]), pack2<TO>(v[2], v[3])};
+        }
+      };
+      auto write = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+          const int q = n * 2 + (eq >> 1);
+          *(u32x2_t*)(wt + buf * kBand16 + er * OROWB + ((q ^ osw(er)) * 16) + (eq & 1) * 8) = w[n];
+        }
+      };
+      auto read = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < kIt16; ++it) {
+          const int e = it * 64 + slane;
+          const int r = e / CH, q = e % CH;
+          val[it] = *(const u32x4_t*)(wt + buf * kBand16 + r * OROWB + ((q ^ osw(r)) * 16));
+        }
+      };
+      // A tile that lies wholly inside C (the common case) stores without per-element tests, from a
+      // wave-uniform base with 32-bit lane offsets: the epilogue is bound by instruction issue (two
+      // waves per SIMD drain 128 accumulators each), so every address and mask instruction counts.
+      const bool inside = row0 + BM <= pe.M && col0 + BN <= pe.N && (int64_t)BM * pe.ldc * 2 < ((int64_t)1 << 31);
+      char* const wave_c = (char*)(Cb + (int64_t)(row0 + wm * Cfg::WTM) * pe.ldc + col0 + wn * Cfg::WTN);
+      const uint32_t band_step = (uint32_t)(16 * pe.ldc * 2);
+      uint32_t lane_off[kIt16];
+#pragma unroll
+      for (int it = 0; it < kIt16; ++it) {
         const int e = it * 64 + slane;
-        const int r = e / CH, q = e % CH;
-        const u32x4_t val = *(const u32x4_t*)(wt + r * OROWB + ((q ^ osw(r)) * 16));
-        const int i = row0 + wm * Cfg::WTM + m * 16 + r;
-        const int j = col0 + wn * Cfg::WTN + q * 8;
-        if (i < pe.M && j < pe.N) {
-          TO* c = Cb + (int64_t)i * pe.ldc + j;
-          if (j + 8 <= pe.N) {
-            __builtin_nontemporal_store(val, (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
-          } else {                                 // ragged right edge: element by element
+        lane_off[it] = (uint32_t)((e / CH) * (int)pe.ldc * 2 + (e % CH) * 16);
+      }
+      auto store = [&](int m) __attribute__((always_inline)) {
+        if (inside) {
 #pragma unroll
-            for (int t2 = 0; t2 < 8; ++t2) {
-              const uint32_t word = val[t2 >> 1];
-              const uint16_t h = (t2 & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xffffu);
-              if (j + t2 < pe.N) ((uint16_t*)c)[t2] = h;
+          for (int it = 0; it < kIt16; ++it)
+            __builtin_nontemporal_store(val[it], (u32x4_t*)(wave_c + (lane_off[it] + (uint32_t)m * band_step)));
+          return;
+        }
+#pragma unroll
+        for (int it = 0; it < kIt16; ++it) {
+          const int e = it * 64 + slane;
+          const int r = e / CH, q = e % CH;
+          const int i = row0 + wm * Cfg::WTM + m * 16 + r;
+          const int j = col0 + wn * Cfg::WTN + q * 8;
+          if (i < pe.M && j < pe.N) {
+            TO* c = Cb + (int64_t)i * pe.ldc + j;
+            if (j + 8 <= pe.N) {
+              __builtin_nontemporal_store(val[it], (u32x4_t*)c);   // C is not read again here: keep it from displacing A and B in L2
+            } else {                               // ragged right edge: element by element
+#pragma unroll
+              for (int t2 = 0; t2 < 8; ++t2) {
+                const uint32_t word = val[it][t2 >> 1];
+                const uint16_t h = (t2 & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xffffu);
+                if (j + t2 < pe.N) ((uint16_t*)c)[t2] = h;
+              }
             }
           }
         }
-      }
+      };
+      values(std::integral_constant<int, 0>());
+      static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) {
+        constexpr int m = decltype(m_c)::value;
+        write(m & 1);
+        if constexpr (m > 0) read((m - 1) & 1);
+        if constexpr (m + 1 < MT) values(std::integral_constant<int, m + 1>());
+        if constexpr (m > 0) store(m - 1);
+      });
+      read((MT - 1) & 1);
+      store(MT - 1);
     };
-    // fp32 through LDS, band m
-    auto drain32 = [&](auto actf, auto m_c) __attribute__((always_inline)) {
-      constexpr int m = decltype(m_c)::value;
-#pragma unroll
-      for (int n = 0; n < NT; ++n) {
-        const int j = col0 + wn * Cfg::WTN + n * 16 + eq * 4;
-        float bv[4];
-        bias4(j, bv);
-        f32x4_t w;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = actf(acc[m][n][e] + bv[e]);
-        const int q = n * 4 + eq;
-        *(f32x4_t*)(wt + er * OROWB32 + ((q ^ (er & 15)) * 16)) = w;
-      }
+    // fp32 through LDS, one band at a time (one staging buffer: a band is twice the bytes)
+    auto drain32_all = [&](auto actf) __attribute__((always_inline)) {
       float* Cf = (float*)pe.C + batch * pe.stride_c;
       const int slane = fresh_lane();
+      constexpr int kIt32 = 16 * CH32 / 64;
+      const bool inside = row0 + BM <= pe.M && col0 + BN <= pe.N && (int64_t)BM * pe.ldc * 4 < ((int64_t)1 << 31);
+      char* const wave_c = (char*)(Cf + (int64_t)(row0 + wm * Cfg::WTM) * pe.ldc + col0 + wn * Cfg::WTN);
+      const uint32_t band_step = (uint32_t)(16 * pe.ldc * 4);
+      uint32_t lane_off[kIt32];
 #pragma unroll
-      for (int it = 0; it < 16 * CH32 / 64; ++it) {
+      for (int it = 0; it < kIt32; ++it) {
         const int e = it * 64 + slane;
-        const int r = e / CH32, q = e % CH32;
-        const f32x4_t val = *(const f32x4_t*)(wt + r * OROWB32 + ((q ^ (r & 15)) * 16));
-        const int i = row0 + wm * Cfg::WTM + m * 16 + r;
-        const int j = col0 + wn * Cfg::WTN + q * 4;
-        if (i < pe.M && j < pe.N) {
-          float* c = Cf + (int64_t)i * pe.ldc + j;
-          if (j + 4 <= pe.N) {
-            if (pe.c_cached) *(f32x4_t*)c = val;    // split-K partials are read by the next kernel
-            else __builtin_nontemporal_store(val, (f32x4_t*)c);
-          } else {
+        lane_off[it] = (uint32_t)((e / CH32) * (int)pe.ldc * 4 + (e % CH32) * 16);
+      }
+      static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) {
+        constexpr int m = decltype(m_c)::value;
 #pragma unroll
-            for (int t2 = 0; t2 < 4; ++t2)
-              if (j + t2 < pe.N) c[t2] = val[t2];
+        for (int n = 0; n < NT; ++n) {
+          float bv[4];
+          bias4(col0 + wn * Cfg::WTN + n * 16 + eq * 4, bv);
+          f32x4_t w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = actf(acc[m][n][e] + bv[e]);
+          const int q = n * 4 + eq;
+          *(f32x4_t*)(wt + er * OROWB32 + ((q ^ (er & 15)) * 16)) = w;
+        }
+#pragma unroll
+        for (int it = 0; it < kIt32; ++it) {
+          const int e = it * 64 + slane;
+          const int r = e / CH32, q = e % CH32;
+          const f32x4_t val = *(const f32x4_t*)(wt + r * OROWB32 + ((q ^ (r & 15)) * 16));
+          if (inside) {
+            f32x4_t* c = (f32x4_t*)(wave_c + (lane_off[it] + (uint32_t)m * band_step));
+            if (pe.c_cached) *c = val;             // split-K partials are read by the next kernel
+            else __builtin_nontemporal_store(val, c);
+            continue;
+          }
+          const int i = row0 + wm * Cfg::WTM + m * 16 + r;
+          const int j = col0 + wn * Cfg::WTN + q * 4;
+          if (i < pe.M && j < pe.N) {
+            float* c = Cf + (int64_t)i * pe.ldc + j;
+            if (j + 4 <= pe.N) {
+              if (pe.c_cached) *(f32x4_t*)c = val;
+              else __builtin_nontemporal_store(val, (f32x4_t*)c);
+            } else {
+#pragma unroll
+              for (int t2 = 0; t2 < 4; ++t2)
+                if (j + t2 < pe.N) c[t2] = val[t2];
+            }
           }
         }
-      }
+      });
     };
     // straight from the accumulator layout (C rows that are not 16-byte aligned)
     auto drain = [&](auto actf) __attribute__((always_inline)) {
@@ -532,9 +600,9 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     auto drain_to = [&](auto actf, auto dest) __attribute__((always_inline)) {
       constexpr int kDest = decltype(dest)::value;
       if constexpr (kDest == 2) {
-        static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) { drain32(actf, m_c); });
+        drain32_all(actf);
       } else if constexpr (kDest == 1) {
-        static_for<0, MT>([&](auto m_c) __attribute__((always_inline)) { drain16(actf, m_c); });
+        drain16_all(actf);
       } else {
         drain(actf);
       }

@@ -50,7 +50,6 @@ hipError_t launch_mfma16(const gemm_plan& pl, const void* A, const void* B, void
   X(128, 128, 2, 2, 2, false)
 #define MI355GEMM_MFMA16P_TILES(X) \
   X(256, 256, 2, 4, 2, true)       \
-  X(256, 256, 2, 2, 2, true)       \
   X(128, 128, 2, 2, 2, true)
 
 #define MI355GEMM_MFMA16_DECLARE(T, TO, BM, BN, WM, WN, G, P)                               \
