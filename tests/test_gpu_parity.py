@@ -402,6 +402,26 @@ def test_full_size_workloads_on_sampled_outputs(g, oracle, name):
     # paper's relative criterion on the sampled entries
     eps = 1e-3 * float(np.sqrt(np.mean(ref["y"] ** 2))) + 1e-30
     assert np.mean(err / (np.abs(ref["y"]) + eps) < 0.01) >= 0.99
+    # whole 256 x 256 tiles, every element: the first and the last tile, tiles whose ids fall into
+    # different classes of the XCD renumbering, and the tiles on both sides of a two-launch seam
+    if w.M >= 256 and w.N >= 256:
+        import re
+        tm, tn = (w.M + 255) // 256, (w.N + 255) // 256
+        tiles = {(0, 0), (tm - 1, tn - 1), (tm // 2, tn // 3), (min(9, tm - 1), min(5, tn - 1)), (tm - 1, 0)}
+        seam = re.search(r"columns=(\d+)\.\.$", info.strip()) or re.search(r"columns=(\d+)\.\.\s", info)
+        if seam:
+            c = int(seam.group(1)) // 256
+            tiles |= {(tm // 2, c - 1), (tm // 2, c), (0, c)}
+        for (ti, tj) in sorted(tiles):
+            i0, j0 = ti * 256, tj * 256
+            ii, jj = np.meshgrid(np.arange(i0, min(i0 + 256, w.M)), np.arange(j0, min(j0 + 256, w.N)), indexing="ij")
+            pi2, pj2 = ii.reshape(-1).astype(np.int64), jj.reshape(-1).astype(np.int64)
+            pb2 = np.full(pi2.size, (ti + tj) % w.batch, dtype=np.int64)
+            ref2 = oracle.ref_gemm_points(oracle_problem(oracle, w), wl.storage_numpy(A), wl.storage_numpy(B),
+                                          None if bias is None else bias.numpy(), pb2, pi2, pj2, want=("y", "t", "s"))
+            err2 = np.abs(wl.to_float64(C)[pb2, pi2, pj2] - ref2["y"])
+            assert np.all(err2 <= e2_bound(w, ref2)), (ti, tj, float((err2 / e2_bound(w, ref2)).max()))
+        say(f"    whole tiles {sorted(tiles)}: ok")
 
 
 def test_split_plan_two_launches(g, oracle):
