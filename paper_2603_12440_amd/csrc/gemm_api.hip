@@ -132,24 +132,17 @@ hipError_t launch_skinny(const gemm_plan& pl, const void* A, const void* B, void
   return hipGetLastError();
 }
 
-template <typename T, int RB, int UNROLL>
-hipError_t launch_skinny_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
-                              const void* bias, hipStream_t s) {
-  skinny_mfma_kernel<T, RB, UNROLL><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
-  return hipGetLastError();
-}
-
-template <typename T, int NS>
-hipError_t launch_skinny_ring(const gemm_plan& pl, const void* A, const void* B, void* C,
-                              const void* bias, hipStream_t s) {
-  skinny_ring_kernel<T, NS><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
-  return hipGetLastError();
-}
-
 template <typename T, int DEPTH, int RB, int WAVES>
 hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B, void* C,
                                const void* bias, hipStream_t s) {
   skinny_stage_kernel<T, DEPTH, RB, WAVES><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
+  return hipGetLastError();
+}
+
+template <typename T, int DEPTH, int RB, int WAVES>
+hipError_t launch_skinny_direct(const gemm_plan& pl, const void* A, const void* B, void* C,
+                                const void* bias, hipStream_t s) {
+  skinny_direct_kernel<T, DEPTH, RB, WAVES><<<pl.grid, pl.block, 0, s>>>(skinny_args(pl, A, B, C, bias));
   return hipGetLastError();
 }
 
@@ -199,23 +192,15 @@ hipError_t launch_skinny_stage(const gemm_plan& pl, const void* A, const void* B
     64 * WAVES, (MB == 1 || (MB == 2 && WAVES <= 4)) ? 16 : MB * kSkinnyKC * 2,            \
     { nullptr, launch_skinny<bf16_t, MB, WAVES>, launch_skinny<f16_t, MB, WAVES> } }
 
-// skinny on the matrix cores: bm = 16 x rows, bn = rows of W per workgroup, bk = k per MFMA
-#define SKINNY_MFMA_CFG(RB, UNROLL)                                                        \
-  { "skinnymfma_r" #RB "_u" #UNROLL, KIND_SKINNY_MFMA, 16, 16 * RB, 32, 256, 4 * RB * 64 * 16, \
-    { nullptr, launch_skinny_mfma<bf16_t, RB, UNROLL>, launch_skinny_mfma<f16_t, RB, UNROLL> } }
-
-// skinny with W staged through registers into wave-private LDS slabs: same panel shape
+// skinny on the matrix cores, W staged through registers into wave-private LDS slabs:
+// bm = 16 x rows, bn = 32 rows of W per workgroup, bk = k per slab
 #define SKINNY_STAGE_CFG(DEPTH, RB)                                                        \
-  { "skinnystage_d" #DEPTH "_b" #RB, KIND_SKINNY_RING, 16, 32, RB / 2, 256, 4 * 48 * RB,     \
+  { "skinnystage_d" #DEPTH "_b" #RB, KIND_SKINNY_PANEL, 16, 32, RB / 2, 256, 4 * 48 * RB,     \
     { nullptr, launch_skinny_stage<bf16_t, DEPTH, RB, 4>, launch_skinny_stage<f16_t, DEPTH, RB, 4> } }
-#define SKINNY_STAGE8_CFG(DEPTH, RB)                                                       \
-  { "skinnystage_d" #DEPTH "_b" #RB "_w8", KIND_SKINNY_RING, 16, 32, RB / 2, 512, 8 * 48 * RB, \
-    { nullptr, launch_skinny_stage<bf16_t, DEPTH, RB, 8>, launch_skinny_stage<f16_t, DEPTH, RB, 8> } }
-// skinny through wave-private LDS rings: bm = 16 x rows, bn = 32 rows of W per workgroup
-#define SKINNY_RING_CFG(NS)                                                                \
-  { "skinnyring_s" #NS, KIND_SKINNY_RING, 16, 32, 64, 256, 4 * NS * 6144,                   \
-    { nullptr, launch_skinny_ring<bf16_t, NS>, launch_skinny_ring<f16_t, NS> } }
-
+// skinny with W staged through LDS and x fragments straight from L2 (16x16x32 MFMA): same panel shape
+#define SKINNY_DIRECT_CFG(DEPTH, RB, WAVES)                                                \
+  { "skinnydirect_d" #DEPTH "_b" #RB "_w" #WAVES, KIND_SKINNY_PANEL, 16, 32, RB / 2, 64 * WAVES, WAVES * 32 * RB, \
+    { nullptr, launch_skinny_direct<bf16_t, DEPTH, RB, WAVES>, launch_skinny_direct<f16_t, DEPTH, RB, WAVES> } }
 const Config kConfigs[] = {
     SIMT_CFG(64, 64, 16),
     SIMT_CFG(32, 32, 16),
@@ -245,16 +230,11 @@ const Config kConfigs[] = {
     SKINNY_CFG(1, 8, 2),
     SKINNY_CFG(2, 8, 1),
     SKINNY_CFG(4, 8, 1),
-    SKINNY_MFMA_CFG(1, 8),
-    SKINNY_MFMA_CFG(1, 16),
-    SKINNY_MFMA_CFG(2, 8),
-    SKINNY_RING_CFG(5),
-    SKINNY_RING_CFG(4),
-    SKINNY_RING_CFG(6),
-    SKINNY_STAGE_CFG(2, 256),
     SKINNY_STAGE_CFG(3, 256),
     SKINNY_STAGE_CFG(2, 512),
-    SKINNY_STAGE8_CFG(2, 256),
+    SKINNY_DIRECT_CFG(2, 512, 4),
+    SKINNY_DIRECT_CFG(3, 512, 4),
+    SKINNY_DIRECT_CFG(2, 256, 8),
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -352,8 +332,8 @@ bool applicable(const Config& c, const gemm_desc_t& d) {
   if (d.M >= ((int64_t)1 << 31) - 512 || d.N >= ((int64_t)1 << 31) - 512 ||
       d.K >= ((int64_t)1 << 31) - 512)
     return false;
-  if (c.kind == KIND_SKINNY || c.kind == KIND_SKINNY_MFMA) return d.M <= c.bm;
-  if (c.kind == KIND_SKINNY_RING)   // 32-bit lane offsets inside a 32-row panel
+  if (c.kind == KIND_SKINNY) return d.M <= c.bm;
+  if (c.kind == KIND_SKINNY_PANEL)   // 32-bit lane offsets inside a 32-row panel
     return d.M <= c.bm && 32 * d.ldb * 2 < ((int64_t)1 << 32) && 32 * d.lda * 2 < ((int64_t)1 << 32) &&
            (d.N + 31) / 32 < ((int64_t)1 << 31);
   // MFMA: per-lane byte offsets inside a tile's row panel are 32-bit.
@@ -434,10 +414,10 @@ int choose(const gemm_desc_t& d) {
   // skinny: up to 4 rows of x on the vector ALUs (smallest padded M that fits, first
   // such entry of the table), up to 16 on the matrix cores
   if (d.M > 4 && d.M <= 16) {
-    // register-staged MFMA kernel: the long-burst variant when there is at most one
-    // workgroup per CU anyway, the lighter one (several workgroups per CU) otherwise
+    // W through wave-private LDS slabs, x fragments straight from L2, 16x16x32 MFMA: two slabs
+    // requested ahead per wave; three when there is at most one workgroup per CU anyway
     const bool one_round = (d.N + 31) / 32 <= num_cus();
-    const int i = find_config(one_round ? "skinnystage_d2_b512" : "skinnystage_d3_b256");
+    const int i = find_config(one_round ? "skinnydirect_d3_b512_w4" : "skinnydirect_d2_b512_w4");
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
   if (d.M <= 4) {
@@ -488,12 +468,8 @@ int fill_launch_shape(gemm_plan& pl) {
     pl.grid = dim3((unsigned)wgs, (unsigned)d.batch, 1);
     pl.group_m = (int)(tm < 8 ? tm : 8);
     pl.xcd_remap = ((tm * tn) % 8 == 0) ? 1 : 0;
-  } else if (c.kind == KIND_SKINNY_RING) {
+  } else if (c.kind == KIND_SKINNY_PANEL) {
     pl.grid = dim3((unsigned)((d.N + c.bn - 1) / c.bn), (unsigned)d.batch, 1);
-  } else if (c.kind == KIND_SKINNY_MFMA) {
-    const int64_t blocks = (d.N + c.bn - 1) / c.bn;
-    const int64_t want = (int64_t)num_cus() * 2;
-    pl.grid = dim3((unsigned)(blocks < want ? blocks : want), (unsigned)d.batch, 1);
   } else {
     // One row of W per wave at a time, rows dealt round-robin: bn workgroups per CU,
     // more only if a wave would otherwise own more rows than the kernel has slots for.

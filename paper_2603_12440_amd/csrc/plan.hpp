@@ -11,8 +11,9 @@
 
 namespace mi355gemm {
 
-enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_MFMA = 3, KIND_SKINNY_RING = 4 };
-// (KIND_SKINNY_RING also covers the register-staged kernel: same panel shape, grid and limits)
+enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_PANEL = 3 };
+// (KIND_SKINNY: vector ALUs, a wave per row of W; KIND_SKINNY_PANEL: matrix cores, a workgroup per
+// 32-row panel of W)
 
 struct Config;
 

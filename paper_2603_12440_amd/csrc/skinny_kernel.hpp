@@ -226,13 +226,9 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
 }
 
 
-// ---- M up to 16 on the matrix cores --------------------------------------------------
-// For more than a few x rows the vector ALUs (and the LDS re-reads of x) fall behind
-// the HBM stream, so the products go to v_mfma_f32_16x16x32: a workgroup owns RB
-// blocks of 16 rows of W, its four waves split K into contiguous quarters (so each
-// wave streams 16 separate, but long, contiguous runs), x fragments come straight
-// from global memory (x is small and stays in L2), and the four partial 16x16 results
-// are added through LDS.  Still bound by the one pass over W, not by the MFMAs.
+// ---- matrix-core products for M up to 16 -------------------------------------------------
+// For more than a few x rows the vector ALUs (and the LDS re-reads of x) fall behind the HBM
+// stream, so the products go to the matrix cores: operands are 8 consecutive k per lane.
 typedef float f32x4acc_t __attribute__((ext_vector_type(4)));
 template <typename T> struct Mfma16;
 template <> struct Mfma16<bf16_t> {
@@ -248,96 +244,6 @@ template <> struct Mfma16<f16_t> {
   }
 };
 
-template <typename T, int RB, int UNROLL>
-__global__ __launch_bounds__(256) void skinny_mfma_kernel(SkinnyArgs p) {
-  __shared__ f32x4acc_t red[4][RB][64];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int col = lane & 15, oct = lane >> 4;         // MFMA operand: row/col lane%16, k-octet lane/16
-  const int64_t batch = blockIdx.y;
-  const T* X = (const T*)p.X + batch * p.stride_x;
-  const T* W = (const T*)p.W + batch * p.stride_w;
-  const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
-
-  const int steps = (p.K + 31) / 32;                  // MFMA k-steps over all of K
-  const int per_wave = (steps + 3) / 4;
-  const int s_begin = wave * per_wave;
-  const int s_end = min(steps, s_begin + per_wave);
-  const bool x_live = col < p.M;                      // x rows past M read as zero
-  const T* xrow = X + (int64_t)min(col, p.M - 1) * p.ldx + oct * 8;
-
-  const int n_blocks = (p.N + 16 * RB - 1) / (16 * RB);
-  for (int blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
-    const int n0 = blk * 16 * RB;
-    const T* wrow[RB];
-#pragma unroll
-    for (int r = 0; r < RB; ++r) wrow[r] = W + (int64_t)min(n0 + r * 16 + col, p.N - 1) * p.ldw + oct * 8;
-
-    f32x4acc_t acc[RB];
-#pragma unroll
-    for (int r = 0; r < RB; ++r) acc[r] = f32x4acc_t{0.f, 0.f, 0.f, 0.f};
-
-    for (int s0 = s_begin; s0 < s_end; s0 += UNROLL) {
-      u32x4_t wv[UNROLL][RB], xv[UNROLL];
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u) {
-        const int k = (s0 + u) * 32;
-        const bool live = (s0 + u < s_end) && (k + oct * 8 < p.K);
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-          wv[u][r] = u32x4_t{0u, 0u, 0u, 0u};
-          // (plain loads: the other half of each 128-byte line is wanted by the next step)
-          if (live) wv[u][r] = *(const u32x4_t*)(wrow[r] + k);
-        }
-        xv[u] = u32x4_t{0u, 0u, 0u, 0u};
-        if (live && x_live) xv[u] = *(const u32x4_t*)(xrow + k);
-      }
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-        for (int r = 0; r < RB; ++r) acc[r] = Mfma16<T>::run(xv[u], wv[u][r], acc[r]);
-    }
-
-    // add the four K quarters; lane l of the result holds rows m = 4*(l/16) + e, column l%16
-    __syncthreads();                                  // previous block's reduction has been read
-#pragma unroll
-    for (int r = 0; r < RB; ++r) red[wave][r][lane] = acc[r];
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int r = 0; r < RB; ++r) {
-        f32x4acc_t t = red[0][r][lane] + red[1][r][lane] + red[2][r][lane] + red[3][r][lane];
-        const int n = n0 + r * 16 + col;
-        if (n < p.N) {
-          const float bv = bias ? bias[n] : 0.0f;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int m = oct * 4 + e;
-            if (m < p.M) {
-              const float v = apply_activation(p.act, t[e] + bv, p.scale);
-              const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
-              if (p.y_f32) ((float*)p.Y)[o] = v;
-              else ((T*)p.Y)[o] = from_float<T>(v);
-            }
-          }
-        }
-      }
-    }
-  }
-}
-
-
-// ---- M up to 16, weights through wave-private LDS rings -----------------------------------
-// The 16x16x32 variant above reads 64 bytes of 16 different rows per load instruction; the
-// memory system prefers whole 128-byte lines.  Here a workgroup owns 32 rows of W, its four
-// waves split K into contiguous quarters, and every wave runs its own ring of NSTAGE slabs
-// (32 rows x 64 columns of W, and the matching 64 columns of up to 16 x rows) filled by
-// direct-to-LDS loads that move full lines, 8 rows per instruction.  The ring is private to
-// the wave, so the K loop needs no workgroup barrier, only vmcnt waits.  Products by
-// v_mfma_f32_32x32x16 (x rows past M are clamped copies and never stored); the four partial
-// 32x32 blocks are added through LDS at the end.
 typedef float f32x16acc_t __attribute__((ext_vector_type(16)));
 template <typename T> struct Mfma32;
 template <> struct Mfma32<bf16_t> {
@@ -353,148 +259,14 @@ template <> struct Mfma32<f16_t> {
   }
 };
 
-template <typename T, int NSTAGE>
-__global__ __launch_bounds__(256) void skinny_ring_kernel(SkinnyArgs p) {
-  constexpr int kSlab = 6144;                          // bytes per stage: W 32 x 128 B, then x 16 x 128 B
-  constexpr int kLoads = 6;                            // direct-to-LDS loads per slab and wave
-  typedef __attribute__((address_space(3))) unsigned char lds_uchar;
-  static_assert(4 * NSTAGE * kSlab >= 4 * 16 * 64 * 4, "the rings double as the reduction buffer");
-  __shared__ __attribute__((aligned(1024))) unsigned char ring[4 * NSTAGE * kSlab];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t batch = blockIdx.y;
-  const T* X = (const T*)p.X + batch * p.stride_x;
-  const T* W = (const T*)p.W + batch * p.stride_w;
-  const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
-  const int n0 = blockIdx.x * 32;
-
-  // slab row r, 16-byte chunk c lives at chunk slot c ^ swz(r) of its 128-byte row
-  auto swz = [](int r) { return (r & 7) ^ ((r >> 3) & 3); };
-  // loads: instruction q covers slab rows 8q .. 8q+7; lane l writes row 8q + l/8, slot l%8
-  uint32_t w_off[4], x_off[2];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int r = q * 8 + lane / 8;
-    const int c = (lane % 8) ^ swz(r);
-    w_off[q] = (uint32_t)(((int64_t)min(n0 + r, p.N - 1) - n0) * p.ldw * 2 + c * 16);
-    if (q < 2) x_off[q] = (uint32_t)((int64_t)min(r, p.M - 1) * p.ldx * 2 + c * 16);
-  }
-  const char* Wb = (const char*)(W + (int64_t)n0 * p.ldw);
-  const char* Xb = (const char*)X;
-  unsigned char* my_ring = ring + wave * (NSTAGE * kSlab);
-  const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_uchar*)my_ring;
-
-  auto issue_slab = [&](int s, int stage) {            // full slab s (64 columns from 64 s)
-    const char* gw = Wb + (int64_t)s * 128;
-    const char* gx = Xb + (int64_t)s * 128;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(ring_lds + stage * kSlab + q * 1024), "v"(w_off[q]), "s"(gw) : "memory", "m0");
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(ring_lds + stage * kSlab + 4096 + q * 1024), "v"(x_off[q]), "s"(gx) : "memory", "m0");
-  };
-
-  // fragments: MFMA 32x32x16 operand lane l = row l%32, k-octet l/32
-  const int fr = lane & 31, fh = lane >> 5;
-  // (x has 16 rows in LDS: the upper half of the x operand repeats them; those outputs are dropped)
-  uint32_t rd[4], rdx[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    rd[kk] = fr * 128 + (((kk * 2 + fh) ^ swz(fr)) * 16);
-    rdx[kk] = (fr & 15) * 128 + (((kk * 2 + fh) ^ swz(fr & 15)) * 16);
-  }
-
-  f32x16acc_t acc;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-
-  auto multiply = [&](int stage, int ksteps) {
-    const unsigned char* s = my_ring + stage * kSlab;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      if (kk < ksteps) {
-        const u32x4_t wf = *(const u32x4_t*)(s + rd[kk]);
-        const u32x4_t xf = *(const u32x4_t*)(s + 4096 + rdx[kk]);
-        acc = Mfma32<T>::run(xf, wf, acc);             // D[x row][W row]
-      }
-    }
-  };
-
-  const int s_full = p.K / 64;                         // full slabs, split over the four waves
-  const int per_wave = (s_full + 3) / 4;
-  const int s_begin = min(wave * per_wave, s_full);
-  const int s_end = min(s_full, s_begin + per_wave);
-  if (s_begin < s_end) {
-#pragma unroll
-    for (int i = 0; i < NSTAGE - 1; ++i) issue_slab(min(s_begin + i, s_end - 1), i);
-    int stage = 0;
-    for (int s = s_begin; s < s_end; ++s) {
-      // slab s has landed when at most the NSTAGE-2 slabs issued after it are outstanding
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * kLoads) : "memory");
-      // refill the stage the previous iteration multiplied from (its reads have been
-      // consumed by MFMAs already issued); past the end, re-load the last slab: same count
-      issue_slab(min(s + NSTAGE - 1, s_end - 1), stage == 0 ? NSTAGE - 1 : stage - 1);
-      multiply(stage, 4);
-      stage = stage + 1 == NSTAGE ? 0 : stage + 1;
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  }
-  if (wave == 3 && s_full * 64 < p.K) {
-    // K tail: zero-filled slab through registers into stage 0 of this wave's ring
-    const int k0 = s_full * 64, kvalid = p.K - k0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = q * 8 + lane / 8;
-      const int c = (lane % 8) ^ swz(r);
-      u32x4_t wv = {0u, 0u, 0u, 0u}, xv = {0u, 0u, 0u, 0u};
-      if (c * 8 < kvalid) {
-        wv = *(const u32x4_t*)(Wb + (int64_t)s_full * 128 + w_off[q]);
-        if (q < 2) xv = *(const u32x4_t*)(Xb + (int64_t)s_full * 128 + x_off[q]);
-      }
-      *(u32x4_t*)(my_ring + q * 1024 + lane * 16) = wv;
-      if (q < 2) *(u32x4_t*)(my_ring + 4096 + q * 1024 + lane * 16) = xv;
-    }
-    multiply(0, (kvalid + 15) / 16);
-  }
-
-  // add the four K quarters (the rings are free now), then bias, activation, store
-  __syncthreads();
-  float* red = (float*)ring;                           // [4 waves][16 regs][64 lanes]
-#pragma unroll
-  for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
-  __syncthreads();
-  // wave w finishes accumulator registers 4w .. 4w+3: x rows 8w + 4*(lane/32) + e, column lane%32
-  // (waves 2 and 3 hold only the repeated rows 16 .. 31 and store nothing)
-  const int n = n0 + fr;
-  const float bv = (bias && n < p.N) ? bias[n] : 0.0f;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int r = wave * 4 + e;
-    const float t = red[(0 * 16 + r) * 64 + lane] + red[(1 * 16 + r) * 64 + lane] +
-                    red[(2 * 16 + r) * 64 + lane] + red[(3 * 16 + r) * 64 + lane];
-    const int m = 8 * wave + 4 * fh + e;
-    if (m < p.M && n < p.N) {
-      const float v = apply_activation(p.act, t + bv, p.scale);
-      const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
-      if (p.y_f32) ((float*)p.Y)[o] = v;
-      else ((T*)p.Y)[o] = from_float<T>(v);
-    }
-  }
-}
-
 // ---- M up to 16, W staged through registers ------------------------------------------
-// Same division of work as the ring kernel (a workgroup owns 32 rows of W, its four or
-// eight waves split K into equal parts, one 32x32x16 MFMA tile per wave, the parts added
-// at the end; eight waves = two per SIMD stream faster when there is one workgroup per CU), but W and x travel global -> registers -> LDS: plain 16-byte loads in which 16
-// (or 32) lanes cover 256 (512) contiguous bytes of a row, DEPTH slabs requested ahead,
-// then ds_write_b128 into one wave-private, swizzled LDS slab from which the MFMA
-// fragments are read back.  For a stream that comes from HBM this moves more bytes per
-// microsecond than direct-to-LDS loads do.
+// A workgroup owns 32 rows of W, its four waves split K into equal contiguous parts, one
+// 32x32x16 MFMA tile per wave (x rows past M are clamped copies and never stored), the parts
+// added through LDS at the end.  W and x travel global -> registers -> LDS: plain 16-byte loads in
+// which 16 (or 32) lanes cover 256 (512) contiguous bytes of a row, DEPTH slabs requested ahead,
+// then ds_write_b128 into one wave-private, swizzled LDS slab from which the MFMA fragments are
+// read back.  The slab is private to the wave, so the K loop needs no workgroup barrier.  For a
+// stream that comes from HBM this moves more bytes per microsecond than direct-to-LDS loads do.
 template <typename T, int DEPTH, int RB, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void skinny_stage_kernel(SkinnyArgs p) {
   constexpr int kRowBytes = RB;                        // RB/2 columns per slab: 256 or 512 bytes of each row
@@ -647,6 +419,177 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_stage_kernel(SkinnyArgs p) 
     const int m = 8 * (r / 4) + 4 * fh + r % 4;
     if (m < p.M && n < p.N) {
       const float v = apply_activation(p.act, t + bv, p.scale);
+      const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
+      if (p.y_f32) ((float*)p.Y)[o] = v;
+      else ((T*)p.Y)[o] = from_float<T>(v);
+    }
+  }
+}
+
+// ---- M up to 16: W staged through LDS, x fragments straight from L2 ------------------------
+// As skinny_stage_kernel (a workgroup owns 32 rows of W, its waves split K into contiguous
+// parts, every wave moves slabs of RB bytes per row global -> registers -> its own swizzled LDS
+// slab -> MFMA fragments), with two changes that shorten everything around the stream:
+//   * the products are v_mfma_f32_16x16x32 on (16 x rows) x (16 W rows), two W tiles per wave,
+//     and the x operand is loaded from global memory directly in fragment layout (lane l: row
+//     l % 16, k-octet l / 16; x is a few hundred KB and stays in L2): no LDS space, writes or
+//     reads for x, a third less LDS traffic;
+//   * with 16 KB (RB = 512) of LDS per wave instead of 24, eight waves fit a CU: two per SIMD,
+//     each with two slabs requested ahead, i.e. 256 KB in flight per CU as in the M = 1 kernel.
+// M <= 4 runs here as well (x rows past M repeat the last row, their results are dropped): the
+// matrix cores do not care, and the vector-ALU kernel's tail of dot products is gone.
+template <typename T, int DEPTH, int RB, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void skinny_direct_kernel(SkinnyArgs p) {
+  constexpr int kRowBytes = RB;                        // RB/2 columns per slab: 256 or 512 bytes of each row
+  constexpr int kCols = RB / 2;
+  constexpr int kWBytes = 32 * kRowBytes;
+  constexpr int kLPR = RB / 16, kRPI = 64 / kLPR;      // lanes per row, rows per load instruction
+  constexpr int kWLoads = 32 / kRPI;                   // 16-byte W loads per lane and slab
+  constexpr int kSteps = kCols / 32;                   // k-steps (MFMAs per W tile) per slab
+  static_assert(WAVES == 4 || WAVES == 8, "K is split over four or eight waves");
+  static_assert(kWBytes >= 8 * 64 * 4, "the slabs double as the reduction buffer");
+  __shared__ __attribute__((aligned(1024))) unsigned char slabs[WAVES * kWBytes];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t batch = blockIdx.y;
+  const T* X = (const T*)p.X + batch * p.stride_x;
+  const T* W = (const T*)p.W + batch * p.stride_w;
+  const float* bias = p.has_bias ? p.bias + batch * p.stride_bias : nullptr;
+  const int n0 = blockIdx.x * 32;
+
+  // W load q of a slab: kLPR lanes cover one row's piece, lane l takes its 16-byte chunk l % kLPR
+  // of slab row kRPI q + l / kLPR; in LDS the chunk sits at slot (chunk ^ row % 16) of its row.
+  const int lr = lane / kLPR, lc = lane % kLPR;
+  // (byte offsets from the panel's first row: 32 bits, the host checks that a panel spans less than 4 GB)
+  const char* const w_base = (const char*)(W + (int64_t)n0 * p.ldw);
+  // LDS slot: (chunk ^ row % 16), and row % 16 = (kRPI q) % 16 + l / kLPR (no carry), so the
+  // lane's part of the xor is fixed and load q's part is a constant
+  const int w_last_row = p.N - 1 - n0;                 // rows past N repeat the last one
+  const uint32_t w_ld_bytes = (uint32_t)p.ldw * 2u, w_src_col = (uint32_t)lc * 16u;
+  const uint32_t w_dst_row = lr * kRowBytes, w_dst_slot0 = (uint32_t)(lc ^ lr) * 16u;
+  // x fragment of k-step kk of a slab: 16 bytes at column 32 kk + 8 (l / 16) of x row l % 16
+  const int fr = lane & 15, fo = lane >> 4;
+  const char* x_src = (const char*)(X + (int64_t)min(fr, p.M - 1) * p.ldx) + fo * 16;
+  unsigned char* mine = slabs + wave * kWBytes;
+
+  // DEPTH slabs of W are on their way at any time; the x fragments (L2 hits) of the next slab only:
+  // they are requested after the current slab's products and before the refill of its W registers,
+  // so waiting for them never waits for a younger W load.
+  u32x4_t wv[DEPTH][kWLoads], xv[kSteps];
+  auto w_src = [&](int q, int row_l) {
+    return (uint32_t)min(kRPI * q + row_l, w_last_row) * w_ld_bytes + w_src_col;
+  };
+  auto load_w = [&](u32x4_t (&w)[kWLoads], int s) {
+    const int64_t off = (int64_t)s * kRowBytes;
+    int row_l = lr;
+    asm volatile("" : "+v"(row_l));                    // the offsets are formed here, not kept in registers
+#pragma unroll
+    for (int q = 0; q < kWLoads; ++q) w[q] = __builtin_nontemporal_load((const u32x4_t*)(w_base + off + w_src(q, row_l)));
+  };
+  auto load_x = [&](u32x4_t (&x)[kSteps], int s) {
+    const int64_t off = (int64_t)s * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < kSteps; ++kk) x[kk] = *(const u32x4_t*)(x_src + off + kk * 64);
+  };
+  auto write_slab = [&](const u32x4_t (&w)[kWLoads]) {
+    uint32_t w_dst_slot = w_dst_slot0;
+    asm volatile("" : "+v"(w_dst_slot));               // the addresses are formed here, not kept in registers
+#pragma unroll
+    for (int q = 0; q < kWLoads; ++q)
+      *(u32x4_t*)(mine + w_dst_row + q * kRPI * kRowBytes + (w_dst_slot ^ (uint32_t)(((kRPI * q) & 15) * 16))) = w[q];
+  };
+  f32x4acc_t acc[2];
+  acc[0] = acc[1] = f32x4acc_t{0.f, 0.f, 0.f, 0.f};
+  auto multiply = [&](const u32x4_t (&x)[kSteps]) {
+    constexpr int kGroup = 2;                          // a group's reads first, then its MFMAs
+#pragma unroll
+    for (int k0 = 0; k0 < kSteps; k0 += kGroup) {
+      u32x4_t wf[2][kGroup];
+#pragma unroll
+      for (int kk = 0; kk < kGroup; ++kk)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          wf[t][kk] = *(const u32x4_t*)(mine + (t * 16 + fr) * kRowBytes + ((((k0 + kk) * 4 + fo) ^ fr) * 16));
+#pragma unroll
+      for (int kk = 0; kk < kGroup; ++kk)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) acc[t] = Mfma16<T>::run(x[k0 + kk], wf[t][kk], acc[t]);   // D[x row][W row]
+    }
+  };
+
+  const int s_full = p.K / kCols;                        // full slabs, split over the waves
+  const int per_wave = (s_full + WAVES - 1) / WAVES;
+  const int s_begin = min(wave * per_wave, s_full);
+  const int s_end = min(s_full, s_begin + per_wave);
+  int s = s_begin;
+  if (s_begin < s_end) load_w(wv[0], s_begin);
+  if (s_begin < s_end) load_x(xv, s_begin);
+#pragma unroll
+  for (int d = 1; d < DEPTH; ++d)
+    if (s_begin + d < s_end) load_w(wv[d], s_begin + d);
+  // steady state: every refill is in range, all loads unconditional
+  for (; s + 2 * DEPTH <= s_end; s += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      write_slab(wv[d]);
+      multiply(xv);
+      load_x(xv, s + d + 1);
+      load_w(wv[d], s + d + DEPTH);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  // the last rounds: registers d hold slab s + d (where that is below s_end)
+  for (; s < s_end; s += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      if (s + d < s_end) {
+        write_slab(wv[d]);
+        multiply(xv);
+        if (s + d + 1 < s_end) load_x(xv, s + d + 1);
+        if (s + d + DEPTH < s_end) load_w(wv[d], s + d + DEPTH);
+      }
+    }
+  }
+  if (wave == WAVES - 1 && s_full * kCols < p.K) {
+    // K tail: chunks past K count as zeros (K is a multiple of 8: chunks are never split)
+    const int k0 = s_full * kCols;
+    const int64_t off = (int64_t)s_full * kRowBytes;
+#pragma unroll
+    for (int q = 0; q < kWLoads; ++q) {
+      wv[0][q] = u32x4_t{0u, 0u, 0u, 0u};
+      if (k0 + lc * 8 < p.K) wv[0][q] = *(const u32x4_t*)(w_base + off + w_src(q, lr));
+    }
+#pragma unroll
+    for (int kk = 0; kk < kSteps; ++kk) {
+      xv[kk] = u32x4_t{0u, 0u, 0u, 0u};
+      if (k0 + kk * 32 + fo * 8 < p.K) xv[kk] = *(const u32x4_t*)(x_src + off + kk * 64);
+    }
+    write_slab(wv[0]);
+    multiply(xv);
+  }
+
+  // add the waves' parts of K (the slabs are free now), then bias, activation, store.
+  // Register r of tile t in lane l: x row 4 (l / 16) + r, W row 16 t + l % 16.
+  __syncthreads();
+  float* red = (float*)slabs;                          // [WAVES][8 regs][64 lanes]
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[(wave * 8 + t * 4 + r) * 64 + lane] = acc[t][r];
+  __syncthreads();
+  constexpr int kPerWave = 8 / WAVES;
+#pragma unroll
+  for (int e = 0; e < kPerWave; ++e) {
+    const int q = wave * kPerWave + e;                 // tile q / 4, register q % 4
+    float sum = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) sum += red[(w * 8 + q) * 64 + lane];
+    const int m = 4 * fo + q % 4;
+    const int n = n0 + (q / 4) * 16 + fr;
+    if (m < p.M && n < p.N) {
+      const float v = apply_activation(p.act, sum + (bias ? bias[n] : 0.0f), p.scale);
       const int64_t o = batch * p.stride_y + (int64_t)m * p.ldy + n;
       if (p.y_f32) ((float*)p.Y)[o] = v;
       else ((T*)p.Y)[o] = from_float<T>(v);

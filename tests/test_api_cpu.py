@@ -222,8 +222,8 @@ def test_kernel_choice(g):
     assert "kernel=skinny_m1_w8_g2" in kernel(M=1, N=28672, K=8192)
     assert "kernel=skinny_m4_w8_g1" in kernel(M=3, N=8192, K=8192)
     for m in (5, 8, 16):
-        assert "kernel=skinnystage_d2_b512" in kernel(M=m, N=8192, K=8192)
-        assert "kernel=skinnystage_d3_b256" in kernel(M=m, N=28672, K=8192)
+        assert "kernel=skinnydirect_d3_b512_w4" in kernel(M=m, N=8192, K=8192)
+        assert "kernel=skinnydirect_d2_b512_w4" in kernel(M=m, N=28672, K=8192)
     assert "grid=256,1,1" in kernel(M=1, N=8192, K=8192)
     assert "kernel=mfma8_256x256x128" in kernel(M=8192, N=8192, K=8192, dtype=g.F8E4M3)
     assert "kernel=mfma8_" in kernel(M=4, N=8192, K=8192, dtype=g.F8E4M3)      # no skinny fp8 kernel
@@ -258,7 +258,7 @@ def test_config_table(g):
         g.gemm_create_config(d, len(names))
     d16 = g.GemmDesc(32, 4096, 4096)
     with pytest.raises(g.GemmError):                                # skinny kernels stop at M = 16
-        g.gemm_create_config(d16, names.index("skinnymfma_r1_u8"))
+        g.gemm_create_config(d16, names.index("skinnydirect_d2_b512_w4"))
 
 
 def test_build_guard_flags_kernels_that_use_scratch_memory():

@@ -124,10 +124,10 @@ def test_all_ones_gives_K(g, K):
     and these K are exact in bf16)."""
     for (M, N, cfg) in [(256, 256, "mfma_256x256x64_w2x2_s2"), (256, 256, "mfma_256x256x32_w2x2_s4"),
                         (130, 70, "mfma_128x128x64_w2x2_s2"), (1, 96, "skinny_m1_w4_g1"),
-                        (8, 33, "skinny_m8_w4_g1"), (16, 33, "skinnymfma_r1_u8"), (9, 70, "skinnymfma_r2_u8"),
-                        (16, 70, "skinnyring_s5"), (3, 33, "skinnyring_s6"),
-                        (16, 70, "skinnystage_d3_b256"), (3, 33, "skinnystage_d2_b512"), (9, 64, "skinnystage_d2_b256"),
-                        (16, 70, "skinnystage_d2_b256_w8"), (5, 33, "skinnystage_d2_b256_w8")]:
+                        (8, 33, "skinny_m8_w4_g1"),
+                        (16, 70, "skinnystage_d3_b256"), (3, 33, "skinnystage_d2_b512"),
+                        (16, 70, "skinnydirect_d2_b512_w4"), (3, 33, "skinnydirect_d2_b256_w8"),
+                        (2, 33, "skinnydirect_d3_b512_w4"), (11, 64, "skinnydirect_d2_b256_w8")]:
         w = wl.Workload("t", M, N, K)
         say(f"all-ones {M}x{N}x{K} {cfg}")
         A = torch.ones((1, M, K), dtype=torch.bfloat16)
@@ -143,15 +143,12 @@ def test_one_hot_k_sweep_copies_columns_of_b(g):
     ks = [0, 1, 7, 8, 15, 16, 31, 32, 63, 64, 65, 127, 128, 191, 192, 255, 256, 319, 320, 327]
     for cfg, M, N in [(c, 300, 260) for c in mfma_configs(g)] + [("skinny_m4_w4_g1", 4, 260),
                                                                 ("skinny_m8_w4_g1", 7, 70),
-                                                                ("skinnymfma_r1_u8", 16, 70),
-                                                                ("skinnymfma_r2_u8", 11, 100),
-                                                                ("skinnyring_s4", 16, 100),
-                                                                ("skinnyring_s6", 5, 70),
                                                                 ("skinnystage_d2_b512", 16, 100),
                                                                 ("skinnystage_d3_b256", 5, 70),
-                                                                ("skinnystage_d2_b256", 13, 33),
-                                                                ("skinnystage_d2_b256_w8", 16, 100),
-                                                                ("skinnystage_d2_b256_w8", 7, 33)]:
+                                                                ("skinnydirect_d2_b512_w4", 16, 100),
+                                                                ("skinnydirect_d2_b256_w8", 5, 70),
+                                                                ("skinnydirect_d3_b512_w4", 9, 70),
+                                                                ("skinnydirect_d2_b512_w4", 3, 33)]:
         w = wl.Workload("t", M, N, K, seed_b=77)
         say(f"one-hot {cfg}")
         A = wl.one_hot_columns(M, K, ks).unsqueeze(0)
@@ -222,11 +219,9 @@ def test_mfma_random_against_oracle(g, oracle, name, changes):
 def test_every_epilogue_on_every_kernel_family(g, oracle, epilogue):
     for (M, N, K, cfg) in [(260, 264, 136, "mfma_256x256x64_w2x2_s2"), (130, 140, 72, "mfma_128x128x64_w2x2_s2"),
                            (3, 515, 264, "skinny_m4_w4_g1"), (8, 100, 1032, "skinny_m8_w4_g1"),
-                           (16, 100, 1032, "skinnymfma_r1_u8"), (5, 70, 264, "skinnymfma_r2_u8"),
-                           (16, 100, 1032, "skinnyring_s4"), (7, 70, 264, "skinnyring_s6"),
                            (16, 100, 1032, "skinnystage_d3_b256"), (7, 70, 264, "skinnystage_d2_b512"),
-                           (11, 40, 2120, "skinnystage_d2_b256"), (16, 100, 1032, "skinnystage_d2_b256_w8"),
-                           (6, 70, 3128, "skinnystage_d2_b256_w8"),
+                           (16, 100, 1032, "skinnydirect_d2_b512_w4"), (7, 70, 264, "skinnydirect_d2_b256_w8"),
+                           (3, 70, 3128, "skinnydirect_d3_b512_w4"), (11, 40, 5192, "skinnydirect_d2_b512_w4"),
                            (70, 90, 50, "simt_64x64x16"), (150, 140, 50, "general_mfma32_128x128x16")]:
         # pre-activations of order 1 so that the activations' curved parts are exercised
         w = wl.Workload("t", M, N, K, dist_a=("normal", 1.0), dist_b=("normal", 1.5 / np.sqrt(K)),
@@ -247,7 +242,7 @@ def test_scaled_epilogues_closed_form_and_tails(g, oracle):
     ts = torch.tensor([0.0, 1.09375, -1.09375, 0.5, -0.5, 8.0, -8.0, 30.0, -30.0, 100.0, -100.0, 200.0,
                        -200.0, 3.0, -3.0, 0.0078125], dtype=torch.float32)
     for (M, cfg) in [(40, "mfma_128x128x64_w2x2_s2"), (300, "mfma_256x256x64_w2x4_s2"), (3, "skinny_m4_w4_g1"),
-                     (16, "skinnystage_d2_b512"), (9, "skinnyring_s5"), (33, "simt_32x32x16")]:
+                     (16, "skinnystage_d2_b512"), (9, "skinnydirect_d2_b512_w4"), (33, "simt_32x32x16")]:
         N, K = 16 * 5, 72
         for epilogue, c in [("swish_scale", 3.0), ("sigmoid_scale_residual", -0.5)]:
             w = wl.Workload("t", M, N, K, epilogue=epilogue, scale=c)
@@ -318,7 +313,7 @@ def test_fp16_random(g, oracle):
 
 def test_batches_and_bias_strides(g, oracle):
     """Each batch reads its own slab; shared bias (stride 0) against one per batch."""
-    for cfg in ("mfma_128x128x64_w2x2_s2", "simt_64x64x16", "skinny_m4_w4_g1", "skinnymfma_r1_u8", "skinnyring_s4",
+    for cfg in ("mfma_128x128x64_w2x2_s2", "simt_64x64x16", "skinny_m4_w4_g1", "skinnydirect_d2_b512_w4", "skinnydirect_d2_b256_w8",
                 "skinnystage_d3_b256"):
         M = 4 if cfg.startswith("skinny") else 96
         w = wl.Workload("t", M, 136, 72, batch=4, epilogue="bias_gelu_erf", seed_a=31, seed_b=32)
