@@ -413,11 +413,11 @@ int64_t split_columns(const gemm_desc_t& d, int big, double single_cost) {
 int choose(const gemm_desc_t& d) {
   // skinny: up to 4 rows of x on the vector ALUs (smallest padded M that fits, first
   // such entry of the table), up to 16 on the matrix cores
-  if (d.M > 4 && d.M <= 16) {
-    // W through wave-private LDS slabs, x fragments straight from L2, 16x16x32 MFMA: two slabs
-    // requested ahead per wave; three when there is at most one workgroup per CU anyway
-    const bool one_round = (d.N + 31) / 32 <= num_cus();
-    const int i = find_config(one_round ? "skinnydirect_d3_b512_w4" : "skinnydirect_d2_b512_w4");
+  if (d.M > 1 && d.M <= 16) {
+    // W through wave-private LDS slabs, x fragments straight from L2, 16x16x32 MFMA, two slabs
+    // requested ahead per wave (M = 16: 24.3 us at N = K = 8192, 80 us at N = 28672; M = 4: 23.0 and
+    // 72 us, where the vector-ALU kernel below needs 26 and 75 us)
+    const int i = find_config("skinnydirect_d2_b512_w4");
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
   if (d.M <= 4) {

@@ -95,16 +95,22 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
   const int first = blockIdx.x * WAVES + wave;          // this wave owns rows first, first + step, ...
   const int step = gridDim.x * WAVES;
   const int n_pass = (p.K + kSkinnyKC - 1) / kSkinnyKC;
+  // Register i of a row holds piece (i + rot) % P, rot different from wave to wave: rows of W are a
+  // power of two apart in most problems, and waves that all read the same columns of their rows at
+  // the same time would crowd the few memory channels those addresses share.
+  static_assert((P & (P - 1)) == 0, "pieces per pass: a power of two");
+  const int rot = first & (P - 1);
+  auto piece = [&](int i) { return ((i + rot) & (P - 1)) * 512 + lane * 8; };   // first column of register i
 
   // One row's current piece: P loads of 16 bytes per lane, all in flight together.
   // Pieces past the end of K read as zero.
   auto load_row = [&](u32x4_t (&wv)[P], int n, int k0) {
-    const T* row = W + (int64_t)n * p.ldw + k0 + lane * 8;
+    const T* row = W + (int64_t)n * p.ldw + k0;
 #pragma unroll
     for (int i = 0; i < P; ++i) {
       wv[i] = u32x4_t{0u, 0u, 0u, 0u};
-      if (k0 + i * 512 + lane * 8 < p.K)
-        wv[i] = __builtin_nontemporal_load((const u32x4_t*)(row + i * 512));
+      if (k0 + piece(i) < p.K)
+        wv[i] = __builtin_nontemporal_load((const u32x4_t*)(row + piece(i)));
     }
   };
   // Dot products of the loaded piece with the staged x rows, reduced over the wave.
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
         if constexpr (kXInRegs) {
           acc[m] = dot8<T>(xr[m][i], wv[i], acc[m]);
         } else {
-          const u32x4_t xv = *(const u32x4_t*)(xs + (m * kSkinnyKC + i * 512 + lane * 8) * 2);
+          const u32x4_t xv = *(const u32x4_t*)(xs + (m * kSkinnyKC + piece(i)) * 2);
           acc[m] = dot8<T>(xv, wv[i], acc[m]);
         }
       }
@@ -150,8 +156,8 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_gemm_kernel(SkinnyArgs p) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
           xr[m][i] = u32x4_t{0u, 0u, 0u, 0u};
-          if (m < p.M && k0 + i * 512 + lane * 8 < p.K)
-            xr[m][i] = *(const u32x4_t*)(X + (int64_t)m * p.ldx + k0 + i * 512 + lane * 8);
+          if (m < p.M && k0 + piece(i) < p.K)
+            xr[m][i] = *(const u32x4_t*)(X + (int64_t)m * p.ldx + k0 + piece(i));
         }
       return;
     }
@@ -478,18 +484,32 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_direct_kernel(SkinnyArgs p)
   // they are requested after the current slab's products and before the refill of its W registers,
   // so waiting for them never waits for a younger W load.
   u32x4_t wv[DEPTH][kWLoads], xv[kSteps];
+  // Full slabs are split over the waves in contiguous parts.  Every workgroup starts its parts at
+  // a different slab and wraps around: the rows of W are a power of two apart in most problems, and
+  // workgroups that all read the same columns of their rows at the same time would crowd the few
+  // memory channels those addresses share.
+  const int s_full = p.K / kCols;
+  const int per_wave = (s_full + WAVES - 1) / WAVES;
+  const int s_first = min(wave * per_wave, s_full);
+  const int s_count = min(s_full, s_first + per_wave) - s_first;
+  const int s_rot = s_count > 0 ? (int)(blockIdx.x % (unsigned)s_count) : 0;
+  auto slab_of = [&](int j) {                          // the wave's j-th slab, 0 <= j < s_count
+    const int r = j + s_rot;
+    return s_first + (r >= s_count ? r - s_count : r);
+  };
+  const int s_begin = 0, s_end = s_count;
   auto w_src = [&](int q, int row_l) {
     return (uint32_t)min(kRPI * q + row_l, w_last_row) * w_ld_bytes + w_src_col;
   };
-  auto load_w = [&](u32x4_t (&w)[kWLoads], int s) {
-    const int64_t off = (int64_t)s * kRowBytes;
+  auto load_w = [&](u32x4_t (&w)[kWLoads], int j) {
+    const int64_t off = (int64_t)slab_of(j) * kRowBytes;
     int row_l = lr;
     asm volatile("" : "+v"(row_l));                    // the offsets are formed here, not kept in registers
 #pragma unroll
     for (int q = 0; q < kWLoads; ++q) w[q] = __builtin_nontemporal_load((const u32x4_t*)(w_base + off + w_src(q, row_l)));
   };
-  auto load_x = [&](u32x4_t (&x)[kSteps], int s) {
-    const int64_t off = (int64_t)s * kRowBytes;
+  auto load_x = [&](u32x4_t (&x)[kSteps], int j) {
+    const int64_t off = (int64_t)slab_of(j) * kRowBytes;
 #pragma unroll
     for (int kk = 0; kk < kSteps; ++kk) x[kk] = *(const u32x4_t*)(x_src + off + kk * 64);
   };
@@ -519,10 +539,6 @@ __global__ __launch_bounds__(64 * WAVES) void skinny_direct_kernel(SkinnyArgs p)
     }
   };
 
-  const int s_full = p.K / kCols;                        // full slabs, split over the waves
-  const int per_wave = (s_full + WAVES - 1) / WAVES;
-  const int s_begin = min(wave * per_wave, s_full);
-  const int s_end = min(s_full, s_begin + per_wave);
   int s = s_begin;
   if (s_begin < s_end) load_w(wv[0], s_begin);
   if (s_begin < s_end) load_x(xv, s_begin);

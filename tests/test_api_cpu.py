@@ -216,14 +216,12 @@ def test_kernel_choice(g):
     # one round and an eighth: the whole round on the big tile, the rest as a second launch
     two = kernel(M=4096, N=4608, K=4096)
     assert "kernel=mfma16_256x256" in two and "columns=0..4095" in two and "columns=4096.." in two
-    for m in (1, 4):
-        assert "kernel=skinny_m" in kernel(M=m, N=8192, K=8192)
     assert "kernel=skinny_m1_w8_g1" in kernel(M=1, N=8192, K=8192)
     assert "kernel=skinny_m1_w8_g2" in kernel(M=1, N=28672, K=8192)
-    assert "kernel=skinny_m4_w8_g1" in kernel(M=3, N=8192, K=8192)
-    for m in (5, 8, 16):
-        assert "kernel=skinnydirect_d3_b512_w4" in kernel(M=m, N=8192, K=8192)
+    for m in (2, 3, 4, 5, 8, 16):
+        assert "kernel=skinnydirect_d2_b512_w4" in kernel(M=m, N=8192, K=8192)
         assert "kernel=skinnydirect_d2_b512_w4" in kernel(M=m, N=28672, K=8192)
+    assert "kernel=skinny_m4_w" in kernel(M=3, N=8192, K=8192, lda=(1 << 27))      # panel offsets need 32 bits
     assert "grid=256,1,1" in kernel(M=1, N=8192, K=8192)
     assert "kernel=mfma8_256x256x128" in kernel(M=8192, N=8192, K=8192, dtype=g.F8E4M3)
     assert "kernel=mfma8_" in kernel(M=4, N=8192, K=8192, dtype=g.F8E4M3)      # no skinny fp8 kernel
