@@ -24,6 +24,7 @@
 #include "mfma16_launch.hpp"
 #include "simt_kernel.hpp"
 #include "general_mfma_kernel.hpp"
+#include "f32_mfma_kernel.hpp"
 #include "skinny_kernel.hpp"
 #include "splitk_kernel.hpp"
 #include "device_check.hpp"
@@ -49,9 +50,8 @@ namespace {
 
 // ---- launchers ---------------------------------------------------------------------
 
-template <typename TIn, typename TOut, int TM, int TN, int TK>
-hipError_t launch_simt_typed(const gemm_plan& pl, const void* A, const void* B, void* C,
-                             const void* bias, hipStream_t s) {
+// the argument block of the general kernels: layouts become element strides
+SimtArgs simt_args(const gemm_plan& pl, const void* A, const void* B, void* C, const void* bias) {
   const gemm_desc_t& d = pl.d;
   SimtArgs a;
   a.A = A; a.B = B; a.C = C; a.bias = (const float*)bias;
@@ -67,6 +67,13 @@ hipError_t launch_simt_typed(const gemm_plan& pl, const void* A, const void* B, 
   a.has_bias = epilogue_has_bias(d.epilogue);
   a.act = epilogue_activation(d.epilogue);
   a.scale = d.scale;
+  return a;
+}
+
+template <typename TIn, typename TOut, int TM, int TN, int TK>
+hipError_t launch_simt_typed(const gemm_plan& pl, const void* A, const void* B, void* C,
+                             const void* bias, hipStream_t s) {
+  const SimtArgs a = simt_args(pl, A, B, C, bias);
   simt_gemm_kernel<TIn, TOut, TM, TN, TK><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
@@ -74,21 +81,7 @@ hipError_t launch_simt_typed(const gemm_plan& pl, const void* A, const void* B, 
 template <typename TIn, typename TOut, int TM, int TN, int TK>
 hipError_t launch_general_mfma_typed(const gemm_plan& pl, const void* A, const void* B, void* C,
                                      const void* bias, hipStream_t s) {
-  const gemm_desc_t& d = pl.d;
-  SimtArgs a;
-  a.A = A; a.B = B; a.C = C; a.bias = (const float*)bias;
-  a.M = d.M; a.N = d.N; a.K = d.K;
-  a.a_si = d.layout_a == GEMM_ROW_MAJOR ? d.lda : 1;
-  a.a_sk = d.layout_a == GEMM_ROW_MAJOR ? 1 : d.lda;
-  a.b_sk = d.layout_b == GEMM_ROW_MAJOR ? d.ldb : 1;
-  a.b_sj = d.layout_b == GEMM_ROW_MAJOR ? 1 : d.ldb;
-  a.c_si = d.layout_c == GEMM_ROW_MAJOR ? d.ldc : 1;
-  a.c_sj = d.layout_c == GEMM_ROW_MAJOR ? 1 : d.ldc;
-  a.stride_a = d.stride_a; a.stride_b = d.stride_b; a.stride_c = d.stride_c;
-  a.stride_bias = d.stride_bias;
-  a.has_bias = epilogue_has_bias(d.epilogue);
-  a.act = epilogue_activation(d.epilogue);
-  a.scale = d.scale;
+  const SimtArgs a = simt_args(pl, A, B, C, bias);
   general_mfma_kernel<TIn, TOut, TM, TN, TK><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
@@ -99,6 +92,37 @@ hipError_t launch_general_mfma(const gemm_plan& pl, const void* A, const void* B
   if (pl.d.dtype_c == GEMM_F32)
     return launch_general_mfma_typed<TIn, float, TM, TN, TK>(pl, A, B, C, bias, s);
   return launch_general_mfma_typed<TIn, TIn, TM, TN, TK>(pl, A, B, C, bias, s);
+}
+
+// fp32 operands in 16-byte pieces (the plan's extents and leading dimensions allow it: applicable());
+// pointers that are not 16-byte aligned take the general kernel on the same grid
+hipError_t launch_f32_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
+                           const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  if (((uintptr_t)A & 15) || ((uintptr_t)B & 15))
+    return launch_general_mfma_typed<float, float, kF32TileM, kF32TileN, 16>(pl, A, B, C, bias, s);
+  const SimtArgs a = simt_args(pl, A, B, C, bias);
+  const bool ak = d.layout_a == GEMM_ROW_MAJOR, bk = d.layout_b == GEMM_COL_MAJOR;   // K contiguous?
+  if (ak && bk) f32_mfma_kernel<true, true><<<pl.grid, pl.block, 0, s>>>(a);
+  else if (ak) f32_mfma_kernel<true, false><<<pl.grid, pl.block, 0, s>>>(a);
+  else if (bk) f32_mfma_kernel<false, true><<<pl.grid, pl.block, 0, s>>>(a);
+  else f32_mfma_kernel<false, false><<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+// small fp32 problems: 16x16 tiles, K split over the waves of a workgroup; each K-contiguous operand
+// is read in float4 groups when its extents, strides and pointer allow it
+hipError_t launch_f32_small(const gemm_plan& pl, const void* A, const void* B, void* C,
+                            const void* bias, hipStream_t s) {
+  const gemm_desc_t& d = pl.d;
+  F32SmallArgs a;
+  a.g = simt_args(pl, A, B, C, bias);
+  a.vec_a = d.layout_a == GEMM_ROW_MAJOR && d.K % 4 == 0 && d.lda % 4 == 0 && d.stride_a % 4 == 0 &&
+            ((uintptr_t)A & 15) == 0;
+  a.vec_b = d.layout_b == GEMM_COL_MAJOR && d.K % 4 == 0 && d.ldb % 4 == 0 && d.stride_b % 4 == 0 &&
+            ((uintptr_t)B & 15) == 0;
+  f32_small_kernel<<<pl.grid, pl.block, 0, s>>>(a);
+  return hipGetLastError();
 }
 
 template <typename TIn, int TM, int TN, int TK>
@@ -161,6 +185,16 @@ hipError_t launch_skinny_direct(const gemm_plan& pl, const void* A, const void* 
     { launch_general_mfma<float, TM, TN, TK>, launch_general_mfma<bf16_t, TM, TN, TK>,     \
       launch_general_mfma<f16_t, TM, TN, TK> } }
 
+// fp32 operands and output moved as float4 groups: 128x128 tiles, slabs of 32 columns of K
+#define F32_MFMA_CFG()                                                                     \
+  { "f32mfma_128x128x32", KIND_F32_VEC, kF32TileM, kF32TileN, kF32TileK, 256,              \
+    (int)(sizeof(float) * 2 * (F32Stage<true>::SIZE + F32Stage<true>::SIZE)),              \
+    { launch_f32_mfma, nullptr, nullptr } }
+
+// small fp32 problems: 16x16 tiles, 256 columns of K per round of the four waves
+#define F32_SMALL_CFG()                                                                    \
+  { "f32small_16x16x256", KIND_SIMT, 16, 16, 256, 256, 4096, { launch_f32_small, nullptr, nullptr } }
+
 #define MFMA_CFG(BM, BN, BK, WM, WN, NS)                                                   \
   { "mfma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, KIND_MFMA, BM, BN, BK,          \
     64 * WM * WN, MfmaTile<bf16_t, BM, BN, BK, WM, WN, NS>::LDS_BYTES,                     \
@@ -220,6 +254,8 @@ const Config kConfigs[] = {
     MFMA8_CFG(256, 256, 128, 2, 4, 2),
     MFMA8_CFG(128, 128, 128, 2, 2, 2),
     MFMA8_CFG(256, 192, 128, 4, 2, 2),
+    F32_MFMA_CFG(),
+    F32_SMALL_CFG(),
     GENERAL_MFMA_CFG(128, 128, 16),
     GENERAL_MFMA_CFG(64, 64, 16),
     SKINNY_CFG(1, 4, 1),
@@ -323,6 +359,13 @@ int resolve(const gemm_desc_t* in, gemm_desc_t* out) {
 bool applicable(const Config& c, const gemm_desc_t& d) {
   if (!c.launch[d.dtype_a]) return false;
   if (c.kind == KIND_SIMT) return true;
+  if (c.kind == KIND_F32_VEC) {
+    // float4 groups along the contiguous index of A and of B: extents, leading dimensions and batch
+    // strides in multiples of 4 elements; fp32 result
+    const bool ak = d.layout_a == GEMM_ROW_MAJOR, bk = d.layout_b == GEMM_COL_MAJOR;
+    return d.dtype_c == GEMM_F32 && d.lda % 4 == 0 && d.ldb % 4 == 0 && d.stride_a % 4 == 0 &&
+           d.stride_b % 4 == 0 && (ak ? d.K : d.M) % 4 == 0 && (bk ? d.K : d.N) % 4 == 0;
+  }
   // The MFMA and skinny kernels take K-contiguous A and B, row-major C, and move
   // 16-byte pieces: every row start must be 16-byte aligned.
   if (d.layout_a != GEMM_ROW_MAJOR || d.layout_b != GEMM_COL_MAJOR || d.layout_c != GEMM_ROW_MAJOR)
@@ -436,15 +479,27 @@ int choose(const gemm_desc_t& d) {
   }
   const int best = best_mfma(d, nullptr);
   if (best >= 0) return best;
-  // general kernels (fp32 operands, or layouts / leading dimensions the tiled kernels do not
-  // take).  Very few tiles: the vector-ALU kernel with 32x32 tiles and the long K step (latency
-  // bound: 256^3 11 us, 512^3 19 us; the matrix-core kernel needs 16 / 28 us there).  Otherwise the
-  // fp32-MFMA kernel: 64x64 tiles (1024^3: 53 us against 76 us on the vector ALUs, 2048^3: 212
-  // against 293 us) until there are four 128x128 tiles per CU (4096^3: 1.47 ms = 93 TFLOP/s
-  // against 2.00 ms).
+  // general kernels (fp32 operands, or layouts / leading dimensions the tiled kernels do not take).
+  //   * fp32, at most four 16x16 tiles per CU: 16x16 tiles with K split over the waves of a workgroup
+  //     (256^3: 6.4 us, 4.3 with a K-contiguous B, against 11 us for the next choice; 512^3: 15 / 11
+  //     against 19 us);
+  //   * very few 32x32 tiles (16-bit operands in layouts the tiled kernels do not take): the vector-ALU
+  //     kernel with 32x32 tiles and the long K step;
+  //   * fp32 in float4 groups and at least one 128x128 tile per CU: the 128x128x32 fp32-MFMA kernel
+  //     (4096^3: 1.2 ms = 113 to 116 TFLOP/s; the general kernel needs 1.47 ms; 2048^3: 205 against 214 us);
+  //   * otherwise the general fp32-MFMA kernel: 64x64 tiles (1024^3: 53 us against 76 us on the vector
+  //     ALUs) until there are four 128x128 tiles per CU.
   const double tiles32 = (double)((d.M + 31) / 32) * (double)((d.N + 31) / 32) * d.batch;
   const double tiles128 = (double)((d.M + 127) / 128) * (double)((d.N + 127) / 128) * d.batch;
+  if (tiles32 <= 1.0 * num_cus()) {             // (tiles32 = a quarter of the 16x16 tiles)
+    const int i = find_config("f32small_16x16x256");
+    if (i >= 0 && applicable(kConfigs[i], d)) return i;
+  }
   if (tiles32 <= 2.0 * num_cus()) return find_config("simt_32x32x64");
+  if (tiles128 >= 1.0 * num_cus()) {
+    const int i = find_config("f32mfma_128x128x32");
+    if (i >= 0 && applicable(kConfigs[i], d)) return i;
+  }
   return find_config(tiles128 >= 4.0 * num_cus() ? "general_mfma32_128x128x16" : "general_mfma32_64x64x16");
 }
 
@@ -454,7 +509,7 @@ int fill_launch_shape(gemm_plan& pl) {
   pl.block = dim3(c.threads, 1, 1);
   pl.group_m = 1;
   pl.xcd_remap = 0;
-  if (c.kind == KIND_SIMT) {
+  if (c.kind == KIND_SIMT || c.kind == KIND_F32_VEC) {
     const int64_t gx = (d.N + c.bn - 1) / c.bn, gy = (d.M + c.bm - 1) / c.bm;
     if (gy > 65535) return GEMM_ERR_BAD_DIM;   // grid.y / grid.z limits
     pl.grid = dim3((unsigned)gx, (unsigned)gy, (unsigned)d.batch);
@@ -737,7 +792,7 @@ static int run_plan(const gemm_plan_t* plan, const void* A, const void* B, void*
   if (epilogue_has_bias(d.epilogue) != (bias != nullptr)) return GEMM_ERR_NULL;
   // The tiled 16-bit kernels move 16-byte pieces; the general kernel only needs
   // element alignment.
-  const uintptr_t in_mask = plan->cfg->kind == KIND_SIMT ? (uintptr_t)esize(d.dtype_a) - 1 : 15;
+  const uintptr_t in_mask = plan->cfg->kind == KIND_SIMT || plan->cfg->kind == KIND_F32_VEC ? (uintptr_t)esize(d.dtype_a) - 1 : 15;
   if (((uintptr_t)A & in_mask) || ((uintptr_t)B & in_mask) ||
       ((uintptr_t)C & ((uintptr_t)esize(d.dtype_c) - 1)) || ((uintptr_t)bias & 3))
     return GEMM_ERR_MISALIGNED;

@@ -11,8 +11,8 @@
 
 namespace mi355gemm {
 
-enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_PANEL = 3 };
-// (KIND_SKINNY: vector ALUs, a wave per row of W; KIND_SKINNY_PANEL: matrix cores, a workgroup per
+enum Kind { KIND_SIMT = 0, KIND_MFMA = 1, KIND_SKINNY = 2, KIND_SKINNY_PANEL = 3, KIND_F32_VEC = 4 };
+// (KIND_F32_VEC: the general kernels' grid, fp32 operands in 16-byte pieces; KIND_SKINNY: vector ALUs, a wave per row of W; KIND_SKINNY_PANEL: matrix cores, a workgroup per
 // 32-row panel of W)
 
 struct Config;

@@ -65,10 +65,11 @@ def pad_minor(t: torch.Tensor, pad: int, fill=float("nan")) -> torch.Tensor:
 
 def run_gpu(g, w: wl.Workload, A: torch.Tensor, B: torch.Tensor, bias, config=-1,
             out_dtype=None, layout_c="row", pad_a=0, pad_b=0, pad_c=0, stride_bias=0,
-            return_plan_info=False):
+            return_plan_info=False, offset_a=0, offset_b=0):
     """A, B: host tensors (batch, major, minor) in storage order.  Returns C as a host
     tensor of logical shape (batch, M, N).  Padding is poisoned with NaN on the inputs
-    and checked to be untouched on the output."""
+    and checked to be untouched on the output.  offset_a / offset_b: elements by which the
+    operand's first element is displaced from its (256-byte aligned) allocation."""
     dev = torch.device("cuda:0")
     Ap, Bp = pad_minor(A, pad_a), pad_minor(B, pad_b)
     lda, ldb = Ap.shape[2], Bp.shape[2]
@@ -77,7 +78,13 @@ def run_gpu(g, w: wl.Workload, A: torch.Tensor, B: torch.Tensor, bias, config=-1
     odt = wl.TORCH_DTYPE[out_dtype or w.out_dtype or w.dtype]
     sentinel = -777.0
     Cd = torch.full((w.batch, c_major, ldc), sentinel, dtype=odt, device=dev)
-    Ad, Bd = Ap.to(dev), Bp.to(dev)
+    def displaced(X, off):
+        if not off:
+            return X.to(dev)
+        buf = torch.zeros(X.numel() + off, dtype=X.dtype, device=dev)
+        buf[off:] = X.to(dev).reshape(-1)
+        return buf[off:].view(X.shape)
+    Ad, Bd = displaced(Ap, offset_a), displaced(Bp, offset_b)
     biasd = bias.to(dev) if bias is not None else None
     desc = gpu_desc(g, w, out_dtype, layout_c, lda, ldb, ldc, stride_bias=stride_bias)
     plan = g.gemm_create_config(desc, config)

@@ -225,11 +225,13 @@ def test_kernel_choice(g):
     assert "grid=256,1,1" in kernel(M=1, N=8192, K=8192)
     assert "kernel=mfma8_256x256x128" in kernel(M=8192, N=8192, K=8192, dtype=g.F8E4M3)
     assert "kernel=mfma8_" in kernel(M=4, N=8192, K=8192, dtype=g.F8E4M3)      # no skinny fp8 kernel
-    assert "kernel=simt_32x32x64" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
-    assert "kernel=simt_32x32x64" in kernel(M=512, N=512, K=512, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=f32small_16x16x256" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=f32small_16x16x256" in kernel(M=512, N=512, K=512, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=simt_32x32x64" in kernel(M=512, N=512, K=512, layout_b=g.ROW_MAJOR)      # 16-bit, general layout
     assert "kernel=general_mfma32_64x64x16" in kernel(M=1024, N=1024, K=1024, dtype=g.F32, layout_b=g.ROW_MAJOR)
-    assert "kernel=general_mfma32_64x64x16" in kernel(M=2048, N=2048, K=2048, dtype=g.F32, layout_b=g.ROW_MAJOR)
-    assert "kernel=general_mfma32_128x128x16" in kernel(M=4096, N=4096, K=4096, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=f32mfma_128x128x32" in kernel(M=2048, N=2048, K=2048, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=f32mfma_128x128x32" in kernel(M=4096, N=4096, K=4096, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=general_mfma32_128x128x16" in kernel(M=4096, N=4096, K=4098, dtype=g.F32, layout_b=g.ROW_MAJOR)
     # 16-bit operands the tiled kernels cannot take go to the general kernel
     assert "kernel=simt" in kernel(M=256, N=256, K=256, layout_a=g.COL_MAJOR)
     assert "kernel=simt" in kernel(M=256, N=256, K=100)            # K not a multiple of 8
@@ -248,9 +250,9 @@ def test_config_table(g):
         try:
             p = g.gemm_create_config(d, i)
         except g.GemmError as e:
-            assert e.status == -9 and not n.startswith(("simt", "general_"))     # fp32 only runs on the general kernels
+            assert e.status == -9 and not n.startswith(("simt", "general_", "f32"))     # fp32 only runs on the general kernels
         else:
-            assert n.startswith(("simt", "general_")) and n in p.info()
+            assert n.startswith(("simt", "general_", "f32")) and n in p.info()
             g.gemm_destroy(p)
     with pytest.raises(g.GemmError):
         g.gemm_create_config(d, len(names))

@@ -282,13 +282,53 @@ def test_skinny_random_against_oracle(g, oracle, M):
         assert_parity(w, C2, ref, A, B, bias)
 
 
+@pytest.mark.parametrize("la,lb,lc", [("row", "row", "row"), ("row", "col", "row"), ("col", "row", "col"),
+                                      ("col", "col", "row")])
+def test_f32_vector_kernel_exact_all_layouts(g, oracle, la, lb, lc):
+    """The fp32 kernel that moves float4 groups: several tiles in both directions, ragged edges, a K
+    tail (K % 32 != 0), padded leading dimensions, a batch, every combination of operand layouts;
+    operands displaced by one element run the general kernel on the same grid instead."""
+    cfg = "f32mfma_128x128x32"
+    w = wl.Workload("t", 300, 260, 72, dtype="f32", layout_a=la, layout_b=lb, epilogue="bias_relu",
+                    seed_a=8, seed_b=9, seed_bias=10)
+    exact_case(g, oracle, w, cfg, layout_c=lc, pad_a=4, pad_b=8, pad_c=3)
+    exact_case(g, oracle, w, cfg, layout_c=lc, offset_a=1)
+    exact_case(g, oracle, w, cfg, layout_c=lc, offset_b=3)
+    w = wl.Workload("t", 68, 36, 20, dtype="f32", layout_a=la, layout_b=lb, batch=3, seed_a=5, seed_b=6)
+    exact_case(g, oracle, w, cfg, layout_c=lc)
+    w = wl.Workload("t", 128, 256, 160, dtype="f32", layout_a=la, layout_b=lb, seed_a=1, seed_b=2)
+    exact_case(g, oracle, w, cfg, layout_c=lc, lo=-40, hi=40)
+    # extents that cannot be cut into float4 groups: the configuration does not apply
+    w = wl.Workload("t", 70, 130, 45, dtype="f32", layout_a=la, layout_b=lb)
+    with pytest.raises(g.GemmError):
+        g.gemm_create_config(gpu_desc(g, w), cfg_index(g, cfg))
+
+
+@pytest.mark.parametrize("la,lb,lc", [("row", "row", "row"), ("row", "col", "row"), ("col", "row", "col"),
+                                      ("col", "col", "row"), ("row", "row", "col")])
+def test_f32_small_kernel_exact_all_layouts(g, oracle, la, lb, lc):
+    """The fp32 kernel for small problems (16x16 tiles, K split over the four waves): ragged edges,
+    K below, at and above one round of 256 columns and not a multiple of 4 (element loads), float4
+    loads with padded leading dimensions, displaced operands, a batch with bias and activation."""
+    cfg = "f32small_16x16x256"
+    for (M, N, K) in [(70, 130, 45), (33, 47, 256), (16, 16, 4), (50, 20, 1500), (100, 36, 772)]:
+        w = wl.Workload("t", M, N, K, dtype="f32", layout_a=la, layout_b=lb, seed_a=M, seed_b=N)
+        exact_case(g, oracle, w, cfg, layout_c=lc)
+    w = wl.Workload("t", 72, 40, 520, dtype="f32", layout_a=la, layout_b=lb, batch=3, epilogue="bias_relu",
+                    seed_a=8, seed_b=9, seed_bias=10)
+    exact_case(g, oracle, w, cfg, layout_c=lc, pad_a=4, pad_b=8, pad_c=3)
+    exact_case(g, oracle, w, cfg, layout_c=lc, pad_a=1, pad_b=2)
+    exact_case(g, oracle, w, cfg, layout_c=lc, offset_a=1, offset_b=2)
+
+
 def test_fp32_config_full_size(g, oracle):
     """The 256^3 fp32 case at full size: true fp32 arithmetic (tolerance 1e-6 forbids
     any narrowing of the operands)."""
     w = wl.WORKLOADS["f32_256"]
     A, B, _ = wl.make_inputs(w)
     ref = run_oracle(oracle, w, A, B, None)
-    for cfg in (None, "simt_64x64x16", "simt_32x32x16", "general_mfma32_128x128x16", "general_mfma32_64x64x16"):
+    for cfg in (None, "simt_64x64x16", "simt_32x32x16", "general_mfma32_128x128x16", "general_mfma32_64x64x16",
+                "f32mfma_128x128x32", "f32small_16x16x256"):
         say(f"f32_256 cfg={cfg}")
         C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg) if cfg else -1)
         r = assert_parity(w, C, ref, A, B, None)
