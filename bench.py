@@ -64,27 +64,32 @@ def parse():
     return ap.parse_args()
 
 
-def source_hash():
-    """Hash of the kernel sources: counter readings taken for another version do not count."""
+def source_hash(files=None):
+    """Hash of kernel sources (`files`: names under csrc/, default all of them): counter readings taken
+    for another version of a kernel do not count."""
     import glob
     import hashlib
+    csrc = os.path.join(ROOT, "paper_2603_12440_amd", "csrc")
+    paths = sorted(glob.glob(os.path.join(csrc, "*"))) if files is None else [os.path.join(csrc, f) for f in sorted(files)]
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2603_12440_amd", "csrc", "*"))):
+    for f in paths:
+        if not os.path.exists(f):
+            return None
         with open(f, "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
 
 
 def measured_traffic(workload):
-    """HBM bytes per launch (fetch + write) from the committed rocprofv3 counter summary,
-    or None if there is none for this workload and this version of the kernels."""
+    """HBM bytes per launch (fetch + write) from the committed rocprofv3 counter summary, or None if
+    there is none for this workload and this version of its kernel (a line names the source files
+    the kernel is compiled from and carries their hash at the time the counters were read)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
         return None
-    cur = source_hash()
     for line in open(path):
         f = line.split()
-        if len(f) >= 5 and not line.startswith("#") and f[0] == workload and f[2] == cur:
+        if len(f) >= 6 and not line.startswith("#") and f[0] == workload and f[2] == source_hash(f[5].split(",")):
             return float(f[3]) + float(f[4])
     return None
 

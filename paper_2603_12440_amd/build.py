@@ -41,7 +41,9 @@ def build_library(verbose: bool = False, only: tuple = ()) -> str:
     flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              # packed-fp32 VALU forms stay off
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage"]
+             "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
+             # keep the generated device assembly next to the object: it is scanned below
+             "-save-temps=obj"]
     noise = ("is not a recognized feature for this target", "-Rpass-analysis=kernel-resource-usage")
 
     def compile_one(src):
@@ -69,12 +71,53 @@ def build_library(verbose: bool = False, only: tuple = ()) -> str:
         raise RuntimeError("kernels that keep data in scratch memory (the hand-scheduled kernels place their own "
                            "waits for asynchronous LDS reads and matrix-core results; a register the compiler "
                            "moves to memory in between breaks that):\n  " + "\n  ".join(bad))
+    hazards = []
+    for src in SOURCES:
+        asm = os.path.join(OBJ_DIR, os.path.splitext(os.path.basename(src))[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+        if os.path.exists(asm):
+            with open(asm) as f:
+                hazards += [f"{os.path.basename(asm)}:{h}" for h in lds_load_hazards(f.read())]
+    if hazards:
+        if os.path.exists(LIB):
+            os.remove(LIB)
+        raise RuntimeError("a direct-to-LDS load reads a scalar register fewer than 5 wait states after a vector-ALU "
+                           "instruction wrote it:\n  " + "\n  ".join(hazards[:20]))
     res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC",
                           "-Wl,--version-script=" + os.path.join(CSRC, "exports.map"), "-o", LIB] + objs,
                          capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("linking failed:\n" + res.stderr)
     return LIB
+
+
+def lds_load_hazards(asm: str) -> list:
+    """Lines of generated assembly where a `global_load_lds_*` takes its scalar base address from a register
+    that a `v_readlane` / `v_readfirstlane` wrote fewer than 5 wait states earlier.  The kernels issue these
+    loads from inline assembly, which the compiler's hazard recogniser does not see into; a vector-memory
+    instruction may not read a scalar register that soon after a vector-ALU write of it."""
+    import re
+    lines = [l.strip() for l in asm.splitlines()]
+    ins = [(i, l) for i, l in enumerate(lines)
+           if l and not l.startswith((";", ".", "//")) and not l.endswith(":")]
+    bad = []
+    for k, (i, l) in enumerate(ins):
+        if not l.startswith("global_load_lds"):
+            continue
+        m = re.search(r"s\[(\d+):(\d+)\]", l)
+        if not m:
+            continue
+        regs = {int(m.group(1)), int(m.group(2))}
+        dist = 0
+        for kk in range(k - 1, max(k - 12, -1), -1):
+            prev = ins[kk][1]
+            w = re.match(r"v_read(?:first)?lane_b32\s+s(\d+)", prev)
+            if w and int(w.group(1)) in regs and dist < 5:
+                bad.append(f"{i + 1}: {l}   (after line {ins[kk][0] + 1}: {prev})")
+            n = re.match(r"s_nop\s+(\d+)", prev)
+            dist += (int(n.group(1)) + 1) if n else 1
+            if dist >= 5:
+                break
+    return bad
 
 
 def kernels_with_scratch(remarks: str) -> list:

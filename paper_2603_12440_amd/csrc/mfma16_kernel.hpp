@@ -208,7 +208,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   // lane l lands at M0 + 16*l): q < A_LOADS fills the A slab, the rest the B slab.  M0 is written
   // by a scalar add; one wait state must pass before the load reads it.  The address pair must
   // not have been written by a vector instruction within five cycles of the load (the hardware
-  // does not check): slab_io produces it long before, and build.py scans the generated code.
+  // does not check): slab_io produces it long before, and the build scans the generated code for it.
   auto issue_one_load = [&](int q, const SlabIo& io) __attribute__((always_inline)) {
     if (q < Cfg::A_LOADS) {
       asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
