@@ -65,14 +65,21 @@ __global__ __launch_bounds__(256) void f32_mfma_kernel(SimtArgs p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int e = tid + u * 256;
-      v[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      // (unconditional loads: a group outside the matrix is read from the matrix's first group
+      // instead and replaced by zeros, so that no load waits for a branch)
+      bool in;
+      const float* src;
       if constexpr (kfast) {
         const int row = e >> 3, c4 = e & 7;
-        if (r0 + row < R && k0 + 4 * c4 < p.K) v[u] = *(const f32x4_t*)(X + (r0 + row) * ld + k0 + 4 * c4);
+        in = r0 + row < R && k0 + 4 * c4 < p.K;
+        src = X + (in ? (r0 + row) * ld + k0 + 4 * c4 : 0);
       } else {
         const int k = e >> 5, c4 = e & 31;
-        if (k0 + k < p.K && r0 + 4 * c4 < R) v[u] = *(const f32x4_t*)(X + (k0 + k) * ld + r0 + 4 * c4);
+        in = k0 + k < p.K && r0 + 4 * c4 < R;
+        src = X + (in ? (k0 + k) * ld + r0 + 4 * c4 : 0);
       }
+      const f32x4_t t = *(const f32x4_t*)src;
+      v[u] = in ? t : f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
   };
   auto stash_one = [&](auto kfast_c, float* S, const f32x4_t (&v)[4]) {
@@ -172,9 +179,11 @@ struct F32SmallArgs {
   int vec_a, vec_b;
 };
 
-__global__ __launch_bounds__(256) void f32_small_kernel(F32SmallArgs q) {
-  const SimtArgs& p = q.g;
-  __shared__ float red[4][4][64];
+// (VEC_A / VEC_B at compile time, one straight-line body each.  Loads are unconditional: a value
+// outside the matrix is read from a valid address of the same row instead and replaced by zero
+// afterwards, so that all of a chunk's loads are in flight together.)
+template <bool VEC_A, bool VEC_B>
+__device__ __forceinline__ void f32_small_body(const SimtArgs& p, float (*red)[4][64]) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int fr = lane & 15, fg = lane >> 4;
@@ -189,32 +198,39 @@ __global__ __launch_bounds__(256) void f32_small_kernel(F32SmallArgs q) {
   const float* b_col = B + (col_ok ? j : 0) * p.b_sj;
 
   // the 16 values of one operand this lane multiplies in the chunk whose first column is k
-  auto fetch = [&](const float* base, int64_t sk, bool ok, bool vec, int64_t k, float (&x)[16]) {
-    if (vec) {
+  auto fetch = [&](auto vec_c, const float* base, int64_t sk, bool ok, int64_t k, float (&x)[16]) {
+    if constexpr (decltype(vec_c)::value) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        f32x4_t t = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        if (ok && k + 4 * c < p.K) t = *(const f32x4_t*)(base + k + 4 * c);
-        x[4 * c] = t[0]; x[4 * c + 1] = t[1]; x[4 * c + 2] = t[2]; x[4 * c + 3] = t[3];
+        const bool in = ok && k + 4 * c < p.K;
+        const f32x4_t t = *(const f32x4_t*)(base + (in ? k + 4 * c : 0));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[4 * c + e] = in ? t[e] : 0.0f;
       }
     } else {
 #pragma unroll
-      for (int s = 0; s < 16; ++s) x[s] = (ok && k + s < p.K) ? base[(k + s) * sk] : 0.0f;
+      for (int s = 0; s < 16; ++s) {
+        const bool in = ok && k + s < p.K;
+        const float t = base[(in ? k + s : 0) * sk];
+        x[s] = in ? t : 0.0f;
+      }
     }
   };
+  using va = std::integral_constant<bool, VEC_A>;
+  using vb = std::integral_constant<bool, VEC_B>;
 
   f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float a0[16], b0[16], a1[16], b1[16];
   const int64_t kl = wave * 64 + fg * 16;               // this lane's first column within a chunk of 256
-  fetch(a_row, p.a_sk, row_ok, q.vec_a, kl, a0);
-  fetch(b_col, p.b_sk, col_ok, q.vec_b, kl, b0);
+  fetch(va(), a_row, p.a_sk, row_ok, kl, a0);
+  fetch(vb(), b_col, p.b_sk, col_ok, kl, b0);
   for (int64_t k0 = 0; k0 < p.K; k0 += 512) {           // two chunks per round: the next one's loads
-    fetch(a_row, p.a_sk, row_ok, q.vec_a, k0 + 256 + kl, a1);   // are on their way during the MFMAs
-    fetch(b_col, p.b_sk, col_ok, q.vec_b, k0 + 256 + kl, b1);
+    fetch(va(), a_row, p.a_sk, row_ok, k0 + 256 + kl, a1);   // are on their way during the MFMAs
+    fetch(vb(), b_col, p.b_sk, col_ok, k0 + 256 + kl, b1);
 #pragma unroll
     for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[s], b0[s], acc, 0, 0, 0);
-    fetch(a_row, p.a_sk, row_ok, q.vec_a, k0 + 512 + kl, a0);
-    fetch(b_col, p.b_sk, col_ok, q.vec_b, k0 + 512 + kl, b0);
+    fetch(va(), a_row, p.a_sk, row_ok, k0 + 512 + kl, a0);
+    fetch(vb(), b_col, p.b_sk, col_ok, k0 + 512 + kl, b0);
 #pragma unroll
     for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[s], b1[s], acc, 0, 0, 0);
   }
@@ -229,6 +245,14 @@ __global__ __launch_bounds__(256) void f32_small_kernel(F32SmallArgs q) {
     const float bj = p.has_bias ? (p.bias + b * p.stride_bias)[j] : 0.0f;
     C[ci * p.c_si + j * p.c_sj] = apply_activation(p.act, t + bj, p.scale);
   }
+}
+
+__global__ __launch_bounds__(256) void f32_small_kernel(F32SmallArgs q) {
+  __shared__ float red[4][4][64];
+  if (q.vec_a && q.vec_b) f32_small_body<true, true>(q.g, red);
+  else if (q.vec_a) f32_small_body<true, false>(q.g, red);
+  else if (q.vec_b) f32_small_body<false, true>(q.g, red);
+  else f32_small_body<false, false>(q.g, red);
 }
 
 }  // namespace mi355gemm

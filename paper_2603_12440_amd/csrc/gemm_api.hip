@@ -481,12 +481,11 @@ int choose(const gemm_desc_t& d) {
   if (best >= 0) return best;
   // general kernels (fp32 operands, or layouts / leading dimensions the tiled kernels do not take).
   //   * fp32, at most four 16x16 tiles per CU: 16x16 tiles with K split over the waves of a workgroup
-  //     (256^3: 6.4 us, 4.3 with a K-contiguous B, against 11 us for the next choice; 512^3: 15 / 11
-  //     against 19 us);
+  //     (256^3: 5 us against 11 us for the next choice; 512^3: 11 to 12 against 19 us);
   //   * very few 32x32 tiles (16-bit operands in layouts the tiled kernels do not take): the vector-ALU
   //     kernel with 32x32 tiles and the long K step;
   //   * fp32 in float4 groups and at least one 128x128 tile per CU: the 128x128x32 fp32-MFMA kernel
-  //     (4096^3: 1.2 ms = 113 to 116 TFLOP/s; the general kernel needs 1.47 ms; 2048^3: 205 against 214 us);
+  //     (4096^3: 1.13 to 1.18 ms = 116 to 122 TFLOP/s; the general kernel needs 1.47 ms; 2048^3: 187 against 220 us);
   //   * otherwise the general fp32-MFMA kernel: 64x64 tiles (1024^3: 53 us against 76 us on the vector
   //     ALUs) until there are four 128x128 tiles per CU.
   const double tiles32 = (double)((d.M + 31) / 32) * (double)((d.N + 31) / 32) * d.batch;
