@@ -1,5 +1,5 @@
 // fp32 GEMM on the matrix cores for operands that can be moved in 16-byte pieces:
-// v_mfma_f32_32x32x2_f32 (exact fp32 products, fp32 accumulation), 128x128 tiles, slabs of 32
+// v_mfma_f32_32x32x2_f32 (exact fp32 products, fp32 accumulation), 128x128 (or 64x64) tiles, slabs of 32
 // columns of K, two LDS buffers and one barrier per slab.  The general kernel next to it takes any
 // element strides at 4 bytes per load and a barrier pair per 16 columns; this one needs the
 // contiguous index of each operand to run in whole, 16-byte aligned float4 groups (the host checks
@@ -12,7 +12,7 @@
 //     two columns of K, one from each half of the wave; which two is free as long as A and B agree,
 //     so lane l multiplies columns 16 (l / 32) + s in step s and reads its 16 values of a slab as
 //     four 16-byte pieces;
-//   * K strided (column-major A / row-major B): [k][128 + 4] floats, one 4-byte read per step.
+//   * K strided (column-major A / row-major B): [k][tile rows + 4] floats, one 4-byte read per step.
 #pragma once
 
 #include "common.hpp"
@@ -20,19 +20,21 @@
 
 namespace mi355gemm {
 
-constexpr int kF32TileM = 128, kF32TileN = 128, kF32TileK = 32;
+constexpr int kF32TileK = 32;
 
-template <bool KFAST> struct F32Stage {
-  static constexpr int ROWS = 128, TK = kF32TileK;
+template <bool KFAST, int ROWS_> struct F32Stage {
+  static constexpr int ROWS = ROWS_, TK = kF32TileK;
   static constexpr int LD = KFAST ? TK + 4 : ROWS + 4;          // floats per LDS row
   static constexpr int SIZE = KFAST ? ROWS * LD : TK * LD;      // floats per buffer
 };
 
-template <bool A_KFAST, bool B_KFAST>
+template <bool A_KFAST, bool B_KFAST, int TM, int TN>
 __global__ __launch_bounds__(256) void f32_mfma_kernel(SimtArgs p) {
-  constexpr int TM = kF32TileM, TN = kF32TileN, TK = kF32TileK;
-  using SA = F32Stage<A_KFAST>;
-  using SB = F32Stage<B_KFAST>;
+  static_assert(TM % 64 == 0 && TN % 64 == 0, "2 x 2 waves of 32x32 tiles");
+  constexpr int TK = kF32TileK;
+  constexpr int MT = TM / 64, NT = TN / 64;                      // 32x32 tiles per wave
+  using SA = F32Stage<A_KFAST, TM>;
+  using SB = F32Stage<B_KFAST, TN>;
   __shared__ __attribute__((aligned(16))) float As[2 * SA::SIZE];
   __shared__ __attribute__((aligned(16))) float Bs[2 * SB::SIZE];
 
@@ -49,21 +51,23 @@ __global__ __launch_bounds__(256) void f32_mfma_kernel(SimtArgs p) {
   const int64_t lda = A_KFAST ? p.a_si : p.a_sk;                 // the strided index of each operand
   const int64_t ldb = B_KFAST ? p.b_sj : p.b_sk;
 
-  f32x16_t acc[2][2];
+  f32x16_t acc[MT][NT];
 #pragma unroll
-  for (int m = 0; m < 2; ++m)
+  for (int m = 0; m < MT; ++m)
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
+    for (int n = 0; n < NT; ++n)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.0f;
 
-  // A slab of either operand is 1024 float4 groups: four per lane.  Groups outside the matrix read
-  // as zeros (extents along the contiguous index are multiples of 4: a group is never split).
-  f32x4_t ra[4], rb[4];
-  auto fetch_one = [&](auto kfast_c, const float* X, int64_t ld, int64_t r0, int64_t R, int64_t k0, f32x4_t (&v)[4]) {
+  // A slab of an operand is ROWS x 32 / 4 float4 groups: ROWS / 32 per lane.  Groups outside the matrix
+  // read as zeros (extents along the contiguous index are multiples of 4: a group is never split).
+  f32x4_t ra[TM / 32], rb[TN / 32];
+  auto fetch_one = [&](auto kfast_c, auto rows_c, const float* X, int64_t ld, int64_t r0, int64_t R, int64_t k0,
+                       f32x4_t (&v)[decltype(rows_c)::value / 32]) {
     constexpr bool kfast = decltype(kfast_c)::value;
+    constexpr int ROWS = decltype(rows_c)::value;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < ROWS / 32; ++u) {
       const int e = tid + u * 256;
       // (unconditional loads: a group outside the matrix is read from the matrix's first group
       // instead and replaced by zeros, so that no load waits for a branch)
@@ -74,7 +78,7 @@ __global__ __launch_bounds__(256) void f32_mfma_kernel(SimtArgs p) {
         in = r0 + row < R && k0 + 4 * c4 < p.K;
         src = X + (in ? (r0 + row) * ld + k0 + 4 * c4 : 0);
       } else {
-        const int k = e >> 5, c4 = e & 31;
+        const int k = e / (ROWS / 4), c4 = e % (ROWS / 4);
         in = k0 + k < p.K && r0 + 4 * c4 < R;
         src = X + (in ? (k0 + k) * ld + r0 + 4 * c4 : 0);
       }
@@ -82,20 +86,21 @@ __global__ __launch_bounds__(256) void f32_mfma_kernel(SimtArgs p) {
       v[u] = in ? t : f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
   };
-  auto stash_one = [&](auto kfast_c, float* S, const f32x4_t (&v)[4]) {
+  auto stash_one = [&](auto kfast_c, auto rows_c, float* S, const f32x4_t (&v)[decltype(rows_c)::value / 32]) {
     constexpr bool kfast = decltype(kfast_c)::value;
-    constexpr int LD = F32Stage<kfast>::LD;
+    constexpr int ROWS = decltype(rows_c)::value;
+    constexpr int LD = F32Stage<kfast, ROWS>::LD;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < ROWS / 32; ++u) {
       const int e = tid + u * 256;
       if constexpr (kfast) *(f32x4_t*)(S + (e >> 3) * LD + 4 * (e & 7)) = v[u];
-      else *(f32x4_t*)(S + (e >> 5) * LD + 4 * (e & 31)) = v[u];
+      else *(f32x4_t*)(S + (e / (ROWS / 4)) * LD + 4 * (e % (ROWS / 4))) = v[u];
     }
   };
   // the 16 values lane l multiplies in one slab, for the 32 rows (columns) from r0 on
-  auto operand = [&](auto kfast_c, const float* S, int r0, float (&x)[16]) {
+  auto operand = [&](auto kfast_c, auto rows_c, const float* S, int r0, float (&x)[16]) {
     constexpr bool kfast = decltype(kfast_c)::value;
-    constexpr int LD = F32Stage<kfast>::LD;
+    constexpr int LD = F32Stage<kfast, decltype(rows_c)::value>::LD;
     if constexpr (kfast) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -109,35 +114,37 @@ __global__ __launch_bounds__(256) void f32_mfma_kernel(SimtArgs p) {
   };
   using a_fast = std::integral_constant<bool, A_KFAST>;
   using b_fast = std::integral_constant<bool, B_KFAST>;
+  using a_rows = std::integral_constant<int, TM>;
+  using b_rows = std::integral_constant<int, TN>;
 
   const int64_t slabs = (p.K + TK - 1) / TK;
-  fetch_one(a_fast(), A, lda, i0, p.M, 0, ra);
-  fetch_one(b_fast(), B, ldb, j0, p.N, 0, rb);
-  stash_one(a_fast(), As, ra);
-  stash_one(b_fast(), Bs, rb);
+  fetch_one(a_fast(), a_rows(), A, lda, i0, p.M, 0, ra);
+  fetch_one(b_fast(), b_rows(), B, ldb, j0, p.N, 0, rb);
+  stash_one(a_fast(), a_rows(), As, ra);
+  stash_one(b_fast(), b_rows(), Bs, rb);
   __syncthreads();
   int buf = 0;
   for (int64_t t = 0; t < slabs; ++t) {
     const bool more = t + 1 < slabs;
     if (more) {
-      fetch_one(a_fast(), A, lda, i0, p.M, (t + 1) * TK, ra);
-      fetch_one(b_fast(), B, ldb, j0, p.N, (t + 1) * TK, rb);
+      fetch_one(a_fast(), a_rows(), A, lda, i0, p.M, (t + 1) * TK, ra);
+      fetch_one(b_fast(), b_rows(), B, ldb, j0, p.N, (t + 1) * TK, rb);
     }
-    float a[2][16], w[2][16];
+    float a[MT][16], w[NT][16];
 #pragma unroll
-    for (int m = 0; m < 2; ++m) operand(a_fast(), As + buf * SA::SIZE, wm * 64 + m * 32, a[m]);
+    for (int m = 0; m < MT; ++m) operand(a_fast(), a_rows(), As + buf * SA::SIZE, wm * (TM / 2) + m * 32, a[m]);
 #pragma unroll
-    for (int n = 0; n < 2; ++n) operand(b_fast(), Bs + buf * SB::SIZE, wn * 64 + n * 32, w[n]);
+    for (int n = 0; n < NT; ++n) operand(b_fast(), b_rows(), Bs + buf * SB::SIZE, wn * (TN / 2) + n * 32, w[n]);
 #pragma unroll
     for (int s = 0; s < 16; ++s)
 #pragma unroll
-      for (int m = 0; m < 2; ++m)
+      for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int n = 0; n < 2; ++n)
+        for (int n = 0; n < NT; ++n)
           acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[m][s], w[n][s], acc[m][n], 0, 0, 0);
     if (more) {
-      stash_one(a_fast(), As + (buf ^ 1) * SA::SIZE, ra);
-      stash_one(b_fast(), Bs + (buf ^ 1) * SB::SIZE, rb);
+      stash_one(a_fast(), a_rows(), As + (buf ^ 1) * SA::SIZE, ra);
+      stash_one(b_fast(), b_rows(), Bs + (buf ^ 1) * SB::SIZE, rb);
     }
     __syncthreads();
     buf ^= 1;
@@ -147,15 +154,15 @@ __global__ __launch_bounds__(256) void f32_mfma_kernel(SimtArgs p) {
   // a store instruction writes 128 contiguous bytes of two rows of a row-major C
   const float* bias = p.has_bias ? p.bias + b * p.stride_bias : nullptr;
 #pragma unroll
-  for (int n = 0; n < 2; ++n) {
-    const int64_t j = j0 + wn * 64 + n * 32 + fr;
+  for (int n = 0; n < NT; ++n) {
+    const int64_t j = j0 + wn * (TN / 2) + n * 32 + fr;
     if (j >= p.N) continue;
     const float bj = bias ? bias[j] : 0.0f;
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
+    for (int m = 0; m < MT; ++m) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t i = i0 + wm * 64 + m * 32 + 8 * (r / 4) + 4 * fh + r % 4;
+        const int64_t i = i0 + wm * (TM / 2) + m * 32 + 8 * (r / 4) + 4 * fh + r % 4;
         if (i >= p.M) continue;
         C[i * p.c_si + j * p.c_sj] = apply_activation(p.act, acc[m][n][r] + bj, p.scale);
       }

@@ -96,17 +96,18 @@ hipError_t launch_general_mfma(const gemm_plan& pl, const void* A, const void* B
 
 // fp32 operands in 16-byte pieces (the plan's extents and leading dimensions allow it: applicable());
 // pointers that are not 16-byte aligned take the general kernel on the same grid
+template <int TM, int TN>
 hipError_t launch_f32_mfma(const gemm_plan& pl, const void* A, const void* B, void* C,
                            const void* bias, hipStream_t s) {
   const gemm_desc_t& d = pl.d;
   if (((uintptr_t)A & 15) || ((uintptr_t)B & 15))
-    return launch_general_mfma_typed<float, float, kF32TileM, kF32TileN, 16>(pl, A, B, C, bias, s);
+    return launch_general_mfma_typed<float, float, TM, TN, 16>(pl, A, B, C, bias, s);
   const SimtArgs a = simt_args(pl, A, B, C, bias);
   const bool ak = d.layout_a == GEMM_ROW_MAJOR, bk = d.layout_b == GEMM_COL_MAJOR;   // K contiguous?
-  if (ak && bk) f32_mfma_kernel<true, true><<<pl.grid, pl.block, 0, s>>>(a);
-  else if (ak) f32_mfma_kernel<true, false><<<pl.grid, pl.block, 0, s>>>(a);
-  else if (bk) f32_mfma_kernel<false, true><<<pl.grid, pl.block, 0, s>>>(a);
-  else f32_mfma_kernel<false, false><<<pl.grid, pl.block, 0, s>>>(a);
+  if (ak && bk) f32_mfma_kernel<true, true, TM, TN><<<pl.grid, pl.block, 0, s>>>(a);
+  else if (ak) f32_mfma_kernel<true, false, TM, TN><<<pl.grid, pl.block, 0, s>>>(a);
+  else if (bk) f32_mfma_kernel<false, true, TM, TN><<<pl.grid, pl.block, 0, s>>>(a);
+  else f32_mfma_kernel<false, false, TM, TN><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }
 
@@ -186,10 +187,10 @@ hipError_t launch_skinny_direct(const gemm_plan& pl, const void* A, const void* 
       launch_general_mfma<f16_t, TM, TN, TK> } }
 
 // fp32 operands and output moved as float4 groups: 128x128 tiles, slabs of 32 columns of K
-#define F32_MFMA_CFG()                                                                     \
-  { "f32mfma_128x128x32", KIND_F32_VEC, kF32TileM, kF32TileN, kF32TileK, 256,              \
-    (int)(sizeof(float) * 2 * (F32Stage<true>::SIZE + F32Stage<true>::SIZE)),              \
-    { launch_f32_mfma, nullptr, nullptr } }
+#define F32_MFMA_CFG(TM, TN)                                                               \
+  { "f32mfma_" #TM "x" #TN "x32", KIND_F32_VEC, TM, TN, kF32TileK, 256,                    \
+    (int)(sizeof(float) * 2 * (F32Stage<true, TM>::SIZE + F32Stage<true, TN>::SIZE)),      \
+    { launch_f32_mfma<TM, TN>, nullptr, nullptr } }
 
 // small fp32 problems: 16x16 tiles, 256 columns of K per round of the four waves
 #define F32_SMALL_CFG()                                                                    \
@@ -254,7 +255,8 @@ const Config kConfigs[] = {
     MFMA8_CFG(256, 256, 128, 2, 4, 2),
     MFMA8_CFG(128, 128, 128, 2, 2, 2),
     MFMA8_CFG(256, 192, 128, 4, 2, 2),
-    F32_MFMA_CFG(),
+    F32_MFMA_CFG(128, 128),
+    F32_MFMA_CFG(64, 64),
     F32_SMALL_CFG(),
     GENERAL_MFMA_CFG(128, 128, 16),
     GENERAL_MFMA_CFG(64, 64, 16),
@@ -484,10 +486,10 @@ int choose(const gemm_desc_t& d) {
   //     (256^3: 5 us against 11 us for the next choice; 512^3: 11 to 12 against 19 us);
   //   * very few 32x32 tiles (16-bit operands in layouts the tiled kernels do not take): the vector-ALU
   //     kernel with 32x32 tiles and the long K step;
-  //   * fp32 in float4 groups and at least one 128x128 tile per CU: the 128x128x32 fp32-MFMA kernel
-  //     (4096^3: 1.13 to 1.18 ms = 116 to 122 TFLOP/s; the general kernel needs 1.47 ms; 2048^3: 187 against 220 us);
-  //   * otherwise the general fp32-MFMA kernel: 64x64 tiles (1024^3: 53 us against 76 us on the vector
-  //     ALUs) until there are four 128x128 tiles per CU.
+  //   * fp32 in float4 groups: the fp32-MFMA kernel with double-buffered slabs, 128x128 tiles from two
+  //     tiles per CU on (4096^3: 1.13 to 1.18 ms = 116 to 122 TFLOP/s; the general kernel needs 1.47 ms),
+  //     64x64 tiles below (2048^3: 184 us, 1024^3: 42 us; general kernel 219 / 53 us);
+  //   * otherwise the general fp32-MFMA kernel: 64x64 tiles until there are four 128x128 tiles per CU.
   const double tiles32 = (double)((d.M + 31) / 32) * (double)((d.N + 31) / 32) * d.batch;
   const double tiles128 = (double)((d.M + 127) / 128) * (double)((d.N + 127) / 128) * d.batch;
   if (tiles32 <= 1.0 * num_cus()) {             // (tiles32 = a quarter of the 16x16 tiles)
@@ -495,8 +497,8 @@ int choose(const gemm_desc_t& d) {
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
   if (tiles32 <= 2.0 * num_cus()) return find_config("simt_32x32x64");
-  if (tiles128 >= 1.0 * num_cus()) {
-    const int i = find_config("f32mfma_128x128x32");
+  {                                             // fp32 in float4 groups: 128x128 tiles from two per CU on
+    const int i = find_config(tiles128 >= 2.0 * num_cus() ? "f32mfma_128x128x32" : "f32mfma_64x64x32");
     if (i >= 0 && applicable(kConfigs[i], d)) return i;
   }
   return find_config(tiles128 >= 4.0 * num_cus() ? "general_mfma32_128x128x16" : "general_mfma32_64x64x16");

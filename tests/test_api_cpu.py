@@ -228,8 +228,9 @@ def test_kernel_choice(g):
     assert "kernel=f32small_16x16x256" in kernel(M=256, N=256, K=256, dtype=g.F32, layout_b=g.ROW_MAJOR)
     assert "kernel=f32small_16x16x256" in kernel(M=512, N=512, K=512, dtype=g.F32, layout_b=g.ROW_MAJOR)
     assert "kernel=simt_32x32x64" in kernel(M=512, N=512, K=512, layout_b=g.ROW_MAJOR)      # 16-bit, general layout
-    assert "kernel=general_mfma32_64x64x16" in kernel(M=1024, N=1024, K=1024, dtype=g.F32, layout_b=g.ROW_MAJOR)
-    assert "kernel=f32mfma_128x128x32" in kernel(M=2048, N=2048, K=2048, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=f32mfma_64x64x32" in kernel(M=1024, N=1024, K=1024, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=general_mfma32_64x64x16" in kernel(M=1024, N=1022, K=1024, dtype=g.F32, layout_b=g.ROW_MAJOR)
+    assert "kernel=f32mfma_64x64x32" in kernel(M=2048, N=2048, K=2048, dtype=g.F32, layout_b=g.ROW_MAJOR)
     assert "kernel=f32mfma_128x128x32" in kernel(M=4096, N=4096, K=4096, dtype=g.F32, layout_b=g.ROW_MAJOR)
     assert "kernel=general_mfma32_128x128x16" in kernel(M=4096, N=4096, K=4098, dtype=g.F32, layout_b=g.ROW_MAJOR)
     # 16-bit operands the tiled kernels cannot take go to the general kernel

@@ -284,11 +284,11 @@ def test_skinny_random_against_oracle(g, oracle, M):
 
 @pytest.mark.parametrize("la,lb,lc", [("row", "row", "row"), ("row", "col", "row"), ("col", "row", "col"),
                                       ("col", "col", "row")])
-def test_f32_vector_kernel_exact_all_layouts(g, oracle, la, lb, lc):
+@pytest.mark.parametrize("cfg", ["f32mfma_128x128x32", "f32mfma_64x64x32"])
+def test_f32_vector_kernel_exact_all_layouts(g, oracle, la, lb, lc, cfg):
     """The fp32 kernel that moves float4 groups: several tiles in both directions, ragged edges, a K
     tail (K % 32 != 0), padded leading dimensions, a batch, every combination of operand layouts;
     operands displaced by one element run the general kernel on the same grid instead."""
-    cfg = "f32mfma_128x128x32"
     w = wl.Workload("t", 300, 260, 72, dtype="f32", layout_a=la, layout_b=lb, epilogue="bias_relu",
                     seed_a=8, seed_b=9, seed_bias=10)
     exact_case(g, oracle, w, cfg, layout_c=lc, pad_a=4, pad_b=8, pad_c=3)
@@ -328,7 +328,7 @@ def test_fp32_config_full_size(g, oracle):
     A, B, _ = wl.make_inputs(w)
     ref = run_oracle(oracle, w, A, B, None)
     for cfg in (None, "simt_64x64x16", "simt_32x32x16", "general_mfma32_128x128x16", "general_mfma32_64x64x16",
-                "f32mfma_128x128x32", "f32small_16x16x256"):
+                "f32mfma_128x128x32", "f32mfma_64x64x32", "f32small_16x16x256"):
         say(f"f32_256 cfg={cfg}")
         C = run_gpu(g, w, A, B, None, config=cfg_index(g, cfg) if cfg else -1)
         r = assert_parity(w, C, ref, A, B, None)
