@@ -182,10 +182,15 @@ def measured_peak(g, dev, bound, dtype):
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
     if bound == "mfma" and dtype in ("bf16", "f16", "f8"):
         code = {"f16": g.F16, "f8": g.F8E4M3}.get(dtype, g.BF16)
-        return {"value": round(g.probe_mfma_peak(code, sink, min_seconds=0.3), 1), "unit": "TFLOP/s",
-                "what": ("v_mfma_f32_32x32x64_f8f6f4" if dtype == "f8" else "v_mfma_f32_32x32x16") +
-                        " register loop, 8 waves per CU, fixed pseudo-random operands",
-                "value_fresh_operands": round(g.probe_mfma_peak(code, sink, min_seconds=0.3, refresh_operands=True), 1)}
+        out = {"value": round(g.probe_mfma_peak(code, sink, min_seconds=0.3), 1), "unit": "TFLOP/s",
+               "what": ("v_mfma_f32_32x32x64_f8f6f4" if dtype == "f8" else "v_mfma_f32_32x32x16") +
+                       " register loop, 8 waves per CU, fixed pseudo-random operands",
+               "value_fresh_operands": round(g.probe_mfma_peak(code, sink, min_seconds=0.3, refresh_operands=True), 1)}
+        if dtype != "f8":            # the shape the default 16-bit kernel multiplies with
+            out["v_mfma_f32_16x16x32"] = {
+                "value": round(g.probe_mfma16_peak(code, sink, min_seconds=0.3), 1),
+                "value_fresh_operands": round(g.probe_mfma16_peak(code, sink, min_seconds=0.3, refresh_operands=True), 1)}
+        return out
     if bound == "hbm":
         n = 5 << 28
         buf = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)

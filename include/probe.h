@@ -36,6 +36,15 @@ int probe_mfma_peak(int dtype, int refresh_operands, void* sink, void* hip_strea
                     double* tflops);
 
 /*
+ * probe_mfma16_peak - the same loop on v_mfma_f32_16x16x32 (dtype GEMM_BF16 or GEMM_F16), the shape
+ * the default 16-bit GEMM kernel multiplies with: 8 waves per CU, the accumulator footprint of a
+ * 128x64 wave block (32 independent 16x16 accumulators per wave), 12 operand registers sets.
+ * Arguments, blocking behaviour and errors as probe_mfma_peak (GEMM_F8E4M3 is refused).
+ */
+int probe_mfma16_peak(int dtype, int refresh_operands, void* sink, void* hip_stream, double min_seconds,
+                      double* tflops);
+
+/*
  * probe_read_peak - streams `bytes` (a multiple of 16384, at least 1 GiB so that the 256 MB
  * last-level cache cannot serve it) from the DEVICE buffer `src` once per launch with the
  * access pattern of the skinny GEMV (a wave reads 16 KB contiguous with 16 loads of 16 bytes

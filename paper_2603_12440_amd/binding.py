@@ -135,6 +135,8 @@ def load_library():
     lib.probe_mfma_peak.restype = ctypes.c_int
     lib.probe_mfma_peak.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double,
                                     ctypes.POINTER(ctypes.c_double)]
+    lib.probe_mfma16_peak.restype = ctypes.c_int
+    lib.probe_mfma16_peak.argtypes = lib.probe_mfma_peak.argtypes
     lib.probe_read_peak.restype = ctypes.c_int
     lib.probe_read_peak.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
@@ -321,6 +323,18 @@ def probe_mfma_peak(dtype: int, sink, stream: Optional[int] = None, min_seconds:
         stream = torch.cuda.current_stream().cuda_stream
     out = ctypes.c_double(0.0)
     _check(load_library().probe_mfma_peak(dtype, int(refresh_operands), _dev_ptr(sink), stream or None,
+                                          min_seconds, ctypes.byref(out)))
+    return out.value
+
+
+def probe_mfma16_peak(dtype: int, sink, stream: Optional[int] = None, min_seconds: float = 0.3,
+                    refresh_operands: bool = False) -> float:
+    """TFLOP/s of an MFMA-only register loop on the 16x16x32 shape on the current device (blocks until done)."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    out = ctypes.c_double(0.0)
+    _check(load_library().probe_mfma16_peak(dtype, int(refresh_operands), _dev_ptr(sink), stream or None,
                                           min_seconds, ctypes.byref(out)))
     return out.value
 

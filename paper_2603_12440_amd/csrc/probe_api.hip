@@ -111,6 +111,59 @@ __global__ __launch_bounds__(512) void mfma_peak_kernel(int steps, float* sink) 
   if (t == 1.2345e38f) *sink = t;                        // never true; keeps the loop alive
 }
 
+// The same loop on v_mfma_f32_16x16x32: the accumulator footprint of a 128x64 wave block of the
+// 256x256 tile (8 x 4 accumulators of 16x16), 8 + 4 operand registers sets, 32 MFMAs per step of
+// 32 columns of K.
+template <typename T> struct ProbeMfma16;
+template <> struct ProbeMfma16<bf16_t> {
+  static __device__ __forceinline__ f32x4_t run(const u32x4_t& a, const u32x4_t& b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+};
+template <> struct ProbeMfma16<f16_t> {
+  static __device__ __forceinline__ f32x4_t run(const u32x4_t& a, const u32x4_t& b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  }
+};
+
+template <typename T, bool REFRESH>
+__global__ __launch_bounds__(512) void mfma16_peak_kernel(int steps, float* sink) {
+  u32x4_t op[12];                                         // 0..7: row fragments, 8..11: column fragments
+  const uint32_t id = (blockIdx.x * 512u + threadIdx.x) * 64u;
+#pragma unroll
+  for (int i = 0; i < 12; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) op[i][e] = ProbeMfma<T>::pair(mix(id + i * 4 + e));
+  f32x4_t acc[8][4];
+#pragma unroll
+  for (int m = 0; m < 8; ++m)
+#pragma unroll
+    for (int n = 0; n < 4; ++n) acc[m][n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  uint32_t rnd = 0x9e3779b9u;
+  for (int s = 0; s < steps; ++s) {
+    if (REFRESH) {
+      rnd = rnd * 1664525u + 1013904223u;                 // wave-uniform: scalar ALU
+      const uint32_t flip = rnd & ProbeMfma<T>::kFlipMask;
+#pragma unroll
+      for (int i = 0; i < 12; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) op[i][e] ^= (i & 1) ? flip : ((flip >> 1) & ProbeMfma<T>::kFlipMask);
+    }
+#pragma unroll
+    for (int m = 0; m < 8; ++m)
+#pragma unroll
+      for (int n = 0; n < 4; ++n) acc[m][n] = ProbeMfma16<T>::run(op[8 + n], op[m], acc[m][n]);
+  }
+  float t = 0.0f;
+#pragma unroll
+  for (int m = 0; m < 8; ++m)
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) t += acc[m][n][r];
+  if (t == 1.2345e38f) *sink = t;                        // never true; keeps the loop alive
+}
+
 template <bool REFRESH>
 __global__ __launch_bounds__(512) void mfma8_peak_kernel(int steps, float* sink) {
   i32x8_t a[4], b[2];
@@ -243,6 +296,32 @@ extern "C" int probe_mfma_peak(int dtype, int refresh_operands, void* sink, void
   if (rc != GEMM_OK) return rc;
   const double flops = 2.0 * 32 * 32 * 16 * kMfmaPerStep * (double)steps * 8.0 * grid;
   *tflops = flops / sec / 1e12;
+  return GEMM_OK;
+}
+
+extern "C" int probe_mfma16_peak(int dtype, int refresh_operands, void* sink, void* hip_stream,
+                                 double min_seconds, double* tflops) {
+  if (!sink || !tflops) return GEMM_ERR_NULL;
+  if (dtype != GEMM_BF16 && dtype != GEMM_F16) return GEMM_ERR_UNSUPPORTED;
+  if (refresh_operands != 0 && refresh_operands != 1) return GEMM_ERR_BAD_ENUM;
+  if ((uintptr_t)sink & 3) return GEMM_ERR_MISALIGNED;
+  if (!(min_seconds >= 0.0)) min_seconds = 0.0;
+  int rc = check_device_gfx950();
+  if (rc != GEMM_OK) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int steps = 2048, grid = 256;                               // ~0.3 ms per launch
+  double sec = 0;
+  float* sk = (float*)sink;
+  if (dtype == GEMM_BF16 && !refresh_operands)
+    rc = timed([&] { mfma16_peak_kernel<bf16_t, false><<<grid, 512, 0, s>>>(steps, sk); }, s, min_seconds, &sec);
+  else if (dtype == GEMM_BF16)
+    rc = timed([&] { mfma16_peak_kernel<bf16_t, true><<<grid, 512, 0, s>>>(steps, sk); }, s, min_seconds, &sec);
+  else if (!refresh_operands)
+    rc = timed([&] { mfma16_peak_kernel<f16_t, false><<<grid, 512, 0, s>>>(steps, sk); }, s, min_seconds, &sec);
+  else
+    rc = timed([&] { mfma16_peak_kernel<f16_t, true><<<grid, 512, 0, s>>>(steps, sk); }, s, min_seconds, &sec);
+  if (rc != GEMM_OK) return rc;
+  *tflops = 2.0 * 16 * 16 * 32 * 32 * (double)steps * 8.0 * grid / sec / 1e12;   // 32 MFMAs per step and wave
   return GEMM_OK;
 }
 

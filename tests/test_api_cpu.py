@@ -33,8 +33,8 @@ def test_every_declared_symbol_is_exported(g):
     assert rope_names == {"rope_apply"}
     probe = open(os.path.join(ROOT, "include", "probe.h")).read()
     probe = re.sub(r"/\*.*?\*/", "", probe, flags=re.S)
-    probe_names = set(re.findall(r"\b(probe_[a-z_]+)\s*\(", probe))
-    assert probe_names == {"probe_mfma_peak", "probe_read_peak"}
+    probe_names = set(re.findall(r"\b(probe_[a-z0-9_]+)\s*\(", probe))
+    assert probe_names == {"probe_mfma_peak", "probe_mfma16_peak", "probe_read_peak"}
     lib = ctypes.CDLL(g.library_path())
     for n in names | rope_names | probe_names:
         assert hasattr(lib, n), n
@@ -49,7 +49,9 @@ def test_binding_exposes_the_same_names(g):
 
 
 def test_probe_argument_checks_need_no_device(g):
-    for call, want in [(lambda: g.probe_mfma_peak(g.BF16, 0, stream=0), -1),
+    for call, want in [(lambda: g.probe_mfma16_peak(g.BF16, 0, stream=0), -1),
+                       (lambda: g.probe_mfma16_peak(g.F8E4M3, 0x1000, stream=0), -4),
+                       (lambda: g.probe_mfma_peak(g.BF16, 0, stream=0), -1),
                        (lambda: g.probe_mfma_peak(g.F32, 0x1000, stream=0), -4),
                        (lambda: g.probe_mfma_peak(7, 0x1000, stream=0), -4),
                        (lambda: g.probe_mfma_peak(g.BF16, 0x1002, stream=0), -5),
