@@ -387,7 +387,7 @@ bool applicable(const Config& c, const gemm_desc_t& d) {
     return false;
   if (c.persist && (d.K % c.bk != 0 || d.K < 2 * c.bk)) return false;   // whole slabs, at least two
   const int64_t tiles = ((d.M + c.bm - 1) / c.bm) * ((d.N + c.bn - 1) / c.bn);
-  return tiles < ((int64_t)1 << 31);
+  return (c.persist ? tiles * d.batch : tiles) < ((int64_t)1 << 31);
 }
 
 int find_config(const char* name) {
@@ -517,11 +517,15 @@ int fill_launch_shape(gemm_plan& pl) {
   } else if (c.kind == KIND_MFMA) {
     const int64_t tm = (d.M + c.bm - 1) / c.bm, tn = (d.N + c.bn - 1) / c.bn;
     int64_t wgs = tm * tn;
-    if (c.persist) {                           // as many workgroups as run at once; each takes every wgs-th tile
+    if (c.persist) {
+      // as many workgroups as run at once; workgroup b takes tiles b, b + wgs, ... of all problems of the batch
       const int64_t at_once = (int64_t)num_cus() * (160 * 1024 / c.lds_bytes);
+      wgs *= d.batch;
       if (wgs > at_once) wgs = at_once;
+      pl.grid = dim3((unsigned)wgs, 1, 1);
+    } else {
+      pl.grid = dim3((unsigned)wgs, (unsigned)d.batch, 1);
     }
-    pl.grid = dim3((unsigned)wgs, (unsigned)d.batch, 1);
     pl.group_m = (int)(tm < 8 ? tm : 8);
     pl.xcd_remap = ((tm * tn) % 8 == 0) ? 1 : 0;
   } else if (c.kind == KIND_SKINNY_PANEL) {

@@ -141,8 +141,12 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
-  const int64_t batch = blockIdx.y;
+  // One tile per workgroup: the batch is the grid's second index.  A persistent workgroup walks over
+  // the tiles of every problem of the batch (tile id = problem * n_tiles + tile within the problem);
+  // `batch` is then the problem of the tile being written out.
+  int batch = PERSIST ? 0 : (int)blockIdx.y;
   const int n_tiles = p.tiles_m * p.tiles_n;
+  const int total_tiles = PERSIST ? n_tiles * p.batches : n_tiles;
 
   // ---- global -> LDS addressing (as in mfma_kernel.hpp, with this kernel's swizzle) -------
   // Load q of this wave fills LDS bytes [slab + (wave*LOADS + q)*1024, +1024): lane l writes
@@ -157,10 +161,11 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   // each epilogue, so that they need not stay in registers across it.)  Leaves ld_a / ld_b at slab `kt`.
   auto load_tile = [&](int vid, int ln, int kt) __attribute__((always_inline)) {
     int tm, tn;
-    tile_coords(p, vid, n_tiles, tm, tn);
+    const int lb = PERSIST ? vid / n_tiles : batch;          // the problem this tile belongs to
+    tile_coords(p, PERSIST ? vid - lb * n_tiles : vid, n_tiles, tm, tn);
     const int r0 = tm * BM, c0 = tn * BN;
-    ld_a = (const char*)((const T*)p.A + batch * p.stride_a + (int64_t)r0 * p.lda) + (int64_t)kt * ROWB;
-    ld_b = (const char*)((const T*)p.B + batch * p.stride_b + (int64_t)c0 * p.ldb) + (int64_t)kt * ROWB;
+    ld_a = (const char*)((const T*)p.A + (int64_t)lb * p.stride_a + (int64_t)r0 * p.lda) + (int64_t)kt * ROWB;
+    ld_b = (const char*)((const T*)p.B + (int64_t)lb * p.stride_b + (int64_t)c0 * p.ldb) + (int64_t)kt * ROWB;
 #pragma unroll
     for (int q = 0; q < Cfg::A_LOADS; ++q) {
       const int r = (wave * Cfg::A_LOADS + q) * RPI + ln / CPR;
@@ -368,7 +373,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     // 4*(l / 16) .. +3 (the operands go in swapped, column fragment first).  For whole-line
     // stores each wave passes one 16-row band of its block at a time through its own piece of
     // the (now idle) LDS: 8- or 16-byte writes in accumulator order, 16-byte reads in row order.
-    const float* bias = pe.has_bias ? pe.bias + batch * pe.stride_bias : nullptr;
+    const float* bias = pe.has_bias ? pe.bias + (int64_t)batch * pe.stride_bias : nullptr;
     const int act = pe.act;
     auto fresh_lane = []() __attribute__((always_inline)) {
       unsigned z = 0;
@@ -419,7 +424,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     constexpr int kBand16 = 16 * OROWB;             // bytes of one staged band
     constexpr int kIt16 = 16 * CH / 64;             // wave-wide 16-byte accesses per band
     auto drain16_all = [&](auto actf) __attribute__((always_inline)) {
-      TO* Cb = (TO*)pe.C + batch * pe.stride_c;
+      TO* Cb = (TO*)pe.C + (int64_t)batch * pe.stride_c;
       const int slane = fresh_lane();
       u32x2_t w[NT];
       u32x4_t val[kIt16];
@@ -504,7 +509,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     };
     // fp32 through LDS, one band at a time (one staging buffer: a band is twice the bytes)
     auto drain32_all = [&](auto actf) __attribute__((always_inline)) {
-      float* Cf = (float*)pe.C + batch * pe.stride_c;
+      float* Cf = (float*)pe.C + (int64_t)batch * pe.stride_c;
       const int slane = fresh_lane();
       constexpr int kIt32 = 16 * CH32 / 64;
       const bool inside = row0 + BM <= pe.M && col0 + BN <= pe.N && (int64_t)BM * pe.ldc * 4 < ((int64_t)1 << 31);
@@ -571,7 +576,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
           const int i = row0 + wm * Cfg::WTM + m * 16 + er;
           if (i >= pe.M || j >= pe.N) continue;
           const bool full = (j + 3 < pe.N);
-          const int64_t o = batch * pe.stride_c + (int64_t)i * pe.ldc + j;
+          const int64_t o = (int64_t)batch * pe.stride_c + (int64_t)i * pe.ldc + j;
           if (pe.c_f32) {
             float* c = (float*)pe.C + o;
             if (full && vec_ok) {
@@ -738,7 +743,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     if (++ld_t == T_full) {
       ld_t = 0;
       ld_vid += gridDim.x;
-      if (ld_vid < n_tiles) load_tile(ld_vid, fresh_lane_id(), 0);   // (no lane id kept in a register across the loop)
+      if (ld_vid < total_tiles) load_tile(ld_vid, fresh_lane_id(), 0);   // (no lane id kept in a register across the loop)
     }
   };
   // tile_end (compile time): the last slab of a tile; its last sub-step requests no fragments (the
@@ -781,8 +786,8 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   }
-  for (int vid = blockIdx.x; vid < n_tiles; vid += gridDim.x) {
-    const bool last = vid + (int)gridDim.x >= n_tiles;
+  for (int vid = blockIdx.x; vid < total_tiles; vid += gridDim.x) {
+    const bool last = vid + (int)gridDim.x >= total_tiles;
     read_all(std::integral_constant<int, 0>());
     for (t = 0; t < T_full - 2; ++t) body(no_t(), true, true);
     body(no_t(), true, !last);
@@ -790,7 +795,8 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     set_prio(0);
     wait_lgkmcnt<0>();
     int tm, tn;
-    tile_coords(p, vid, n_tiles, tm, tn);
+    batch = vid / n_tiles;
+    tile_coords(p, vid - batch * n_tiles, n_tiles, tm, tn);
     epilogue(tm * BM, tn * BN);
     if (!last) {
       // the lane-dependent offsets and addresses are derived afresh here (from an opaque copy of the

@@ -27,13 +27,14 @@ hipError_t launch_mfma16(const gemm_plan& pl, const void* A, const void* B, void
   a.group_m = pl.group_m;
   a.xcd_remap = pl.xcd_remap;
   a.c_cached = pl.c_cached;
+  a.batches = (int)d.batch;
   if constexpr (PERSIST) {
     // The persistent kernel only has the staged output routes (whole-line stores): C rows that are
     // not 16-byte aligned run one tile per workgroup instead.
     const int64_t unit = a.c_f32 ? 4 : 8;
     const bool staged = d.ldc % unit == 0 && d.stride_c % unit == 0 && ((uintptr_t)C & 15) == 0;
     if (!staged) {
-      const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), pl.grid.y, 1);
+      const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)d.batch, 1);
       mfma16_gemm_kernel<T, TO, BM, BN, WM, WN, G, false><<<grid, pl.block, 0, s>>>(a);
       return hipGetLastError();
     }

@@ -31,6 +31,7 @@ struct MfmaArgs {
   int group_m;                 // tile rows per scheduling group
   int xcd_remap;               // 1: spread consecutive tile ids within one XCD
   int c_cached;                // 1: fp32 C is read again right away (split-K partials): ordinary stores
+  int batches;                 // problems in the batch (persistent workgroups walk over the tiles of all of them)
 };
 
 // ---- MFMA wrappers -----------------------------------------------------------

@@ -28,6 +28,7 @@ hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* 
   a.group_m = pl.group_m;
   a.xcd_remap = pl.xcd_remap;
   a.c_cached = pl.c_cached;
+  a.batches = (int)d.batch;
   mfma_gemm_kernel<T, TO, BM, BN, BK, WM, WN, NS><<<pl.grid, pl.block, 0, s>>>(a);
   return hipGetLastError();
 }

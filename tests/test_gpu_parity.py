@@ -730,7 +730,10 @@ def test_persistent_workgroups_exact(g, oracle):
         tile = 128 if "128x128" in cfg else 256
         per_round = 512 if tile == 128 else 256            # workgroups the chip holds at once
         for (tiles_m, tiles_n, K, batch) in [(2, 3, 128, 1), (17, 17, 192, 1), (24, 23, 128, 1), (3, 2, 320, 3),
-                                             (33, 20, 128, 1)]:
+                                             (33, 20, 128, 1),
+                                             # a workgroup's tiles belong to different problems of the batch
+                                             (4, 4, 128, 40 if tile == 128 else 20), (2, 2, 192, 150 if tile == 128 else 70),
+                                             (3, 1, 128, 200 if tile == 128 else 100)]:
             if tile == 256 and tiles_m * tiles_n > 300:
                 continue                                    # (keeps the oracle's share of the test short)
             M, N = tiles_m * tile - 5, tiles_n * tile - 12
