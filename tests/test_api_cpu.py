@@ -67,7 +67,7 @@ def test_probe_argument_checks_need_no_device(g):
 def test_splitk_plans(g):
     """Split-K planning is host work: slices, workspace size, what it refuses."""
     p = g.gemm_create_splitk(g.GemmDesc(512, 512, 32768))
-    assert "kernel=splitk_16+mfma16_128x128" in p.info() and "grid=16,16,1" in p.info()
+    assert "kernel=splitk_16+mfma16_128x128" in p.info() and "grid=256,1,1" in p.info()   # 16 tiles x 16 slices, persistent
     assert g.gemm_workspace_bytes(p) == 16 * 512 * 512 * 4
     # a split-K plan cannot run without its workspace
     with pytest.raises(g.GemmError) as e:
