@@ -364,6 +364,18 @@ def test_batches_and_bias_strides(g, oracle):
             C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg), stride_bias=sb)
             ref = run_oracle(oracle, w, A, B, bias, stride_bias=sb)
             assert_parity(w, C, ref, A, B, bias)
+    # a bias stride that is not a multiple of 4 floats: the bias vectors of batches 1..3 start at addresses
+    # that are only 4-byte aligned (the matrix-core epilogues read the bias in 16-byte pieces where they can)
+    for cfg in ("mfma16_256x256x64_w2x4", "mfma16_128x128x64_w2x2", "mfma16_256x256x64_w2x4_p", "mfma16_128x128x64_w2x2_p",
+                "mfma_128x128x64_w2x2_s2", "mfma_256x256x64_w2x4_s2"):
+        w = wl.Workload("t", 300, 264, 128, batch=4, epilogue="bias_relu", seed_a=41, seed_b=42)
+        A, B, _ = wl.make_inputs(w)
+        bias = wl._draw(("uniform", 1.0), (3 * 265 + 264,), 43)
+        say(f"batched {cfg} stride_bias=265")
+        for od in (None, "f32"):
+            C = run_gpu(g, w, A, B, bias, config=cfg_index(g, cfg), stride_bias=265, out_dtype=od)
+            ref = run_oracle(oracle, w, A, B, bias, stride_bias=265)
+            assert_parity(w, C, ref, A, B, bias, out_dtype=od)
     # constant per batch: C_b = K (b+1)^2
     w = wl.Workload("t", 64, 64, 64, batch=3)
     A = torch.stack([torch.full((64, 64), float(b + 1)) for b in range(3)]).to(torch.bfloat16)
