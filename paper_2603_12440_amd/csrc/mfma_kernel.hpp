@@ -425,6 +425,12 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLater * kLoadsPerSlab) : "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    // Two waves share a SIMD: the one that has just passed the hand-over runs its last k-step (and
+    // issues the refill) at high priority, then drops; the wave that is behind gets the matrix pipe.
+    if (Cfg::kWaves > 4) asm volatile("s_setprio 3" ::: "memory");
+  };
+  auto drop_prio = [&]() __attribute__((always_inline)) {
+    if (Cfg::kWaves > 4) asm volatile("s_setprio 0" ::: "memory");
   };
 
   if (T_full > 0) {
@@ -441,6 +447,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       hand_over(std::integral_constant<int, D - 2>());
       // (min: t + D <= T_full - 1 here; written out, it keeps the slab address in scalar registers)
       step((KK - 1) & 1, true, next_stage, 0, true, min(t + D, T_full - 1), stage);
+      drop_prio();
       stage = next_stage;
     }
     for (; t < T_full; ++t) {                  // the last D slabs: nothing left to prefetch
@@ -449,6 +456,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       for (int kk = 0; kk < KK - 1; ++kk) step(kk & 1, true, stage, kk + 1, false, 0, 0);
       hand_over(std::integral_constant<int, 0>());
       step((KK - 1) & 1, true, next_stage, 0, false, 0, 0);
+      drop_prio();
       stage = next_stage;
     }
     // the last fragment reads (of a stage nobody multiplies) are still in flight
