@@ -377,7 +377,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
   // of C and runs of 4 consecutive columns: that is what the stores want.
   auto step = [&](int cur, bool reads, int rs, int rk, bool loads, int lk, int ls) __attribute__((always_inline)) {
     constexpr int kLoads = Cfg::A_LOADS + Cfg::B_LOADS;
-    constexpr int kLeft = Ord::kMfma > Ord::kReads ? Ord::kMfma - Ord::kReads : 1;
+    constexpr int kLeft = Ord::kMfma;
     constexpr int kPer = (kLoads + kLeft - 1) / kLeft;
 #pragma unroll
     for (int i = 0; i < Ord::kMfma; ++i) {
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma_gemm_kernel(MfmaArgs p) {
       Frag<T>::mfma(bf[cur][n], af[cur][m], acc[m][n]);
       if (reads && i < Ord::kReads) read_one(i, rs, rk, cur ^ 1);
       if (loads) {
-        const int j = Ord::kMfma > Ord::kReads ? i - Ord::kReads : i;
+        const int j = i;
         if (j >= 0) {
 #pragma unroll
           for (int q = j * kPer; q < (j + 1) * kPer && q < kLoads; ++q) issue_one_load(q, lk, ls);
