@@ -247,10 +247,8 @@ const Config kConfigs[] = {
     MFMA16_CFG(128, 128, 2, 2, 2),
     MFMA_CFG(256, 256, 64, 2, 4, 2),
     MFMA_CFG(256, 256, 64, 2, 2, 2),
-    MFMA_CFG(256, 256, 32, 2, 2, 4),
     MFMA_CFG(256, 128, 64, 2, 2, 2),
     MFMA_CFG(128, 128, 64, 2, 2, 2),
-    MFMA_CFG(256, 256, 64, 4, 4, 2),
     MFMA_CFG(256, 192, 64, 4, 2, 2),
     MFMA8_CFG(256, 256, 128, 2, 4, 2),
     MFMA8_CFG(128, 128, 128, 2, 2, 2),

@@ -37,10 +37,8 @@ hipError_t launch_mfma(const gemm_plan& pl, const void* A, const void* B, void* 
 #define MI355GEMM_MFMA_TILES(X) \
   X(256, 256, 64, 2, 4, 2)      \
   X(256, 256, 64, 2, 2, 2)      \
-  X(256, 256, 32, 2, 2, 4)      \
   X(256, 128, 64, 2, 2, 2)      \
   X(128, 128, 64, 2, 2, 2)      \
-  X(256, 256, 64, 4, 4, 2)      \
   X(256, 192, 64, 4, 2, 2)
 // fp8 operands (BK is twice as many values: the same slabs in bytes):
 #define MI355GEMM_MFMA8_TILES(X) \

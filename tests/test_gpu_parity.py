@@ -122,7 +122,7 @@ def test_general_kernel_exact_all_layouts(g, oracle, dtype, la, lb, lc):
 def test_all_ones_gives_K(g, K):
     """Every k contributes exactly once (K and all partial sums are exact in fp32,
     and these K are exact in bf16)."""
-    for (M, N, cfg) in [(256, 256, "mfma_256x256x64_w2x2_s2"), (256, 256, "mfma_256x256x32_w2x2_s4"),
+    for (M, N, cfg) in [(256, 256, "mfma_256x256x64_w2x2_s2"), (256, 256, "mfma16_256x256x64_w2x4"),
                         (130, 70, "mfma_128x128x64_w2x2_s2"), (1, 96, "skinny_m1_w4_g1"),
                         (8, 33, "skinny_m8_w4_g1"),
                         (16, 70, "skinnystage_d3_b256"), (3, 33, "skinnystage_d2_b512"),
@@ -719,8 +719,6 @@ def test_k_tail_every_length_on_every_mfma_tile(g):
     for cfg in mfma_configs(g) + F8_CONFIGS:
         f8 = cfg.startswith("mfma8")
         dt, piece, slab = ("f8", 16, 128) if f8 else ("bf16", 8, 64)
-        if cfg.startswith("mfma_256x256x32"):
-            slab = 32
         for K in [p for p in range(piece, slab, piece)] + [slab + p for p in range(piece, slab, piece)]:
             w = wl.Workload("t", 130, 132, K, dtype=dt, out_dtype="f32")
             sa, sb = wl.operand_shapes(w)
