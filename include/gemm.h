@@ -7,8 +7,8 @@
  * accumulated in fp32 whatever the storage type; the epilogue runs in fp32 on
  * the accumulators and the result is rounded once (to nearest even) to C's
  * storage type.  The operation is the matmul-with-post-op workload class of
- * the paper's evaluation (Sec. 4, Tab. "operations": "Matmul with relu
- * post-op"; App. "Per-task results": matmul + GELU / activation tasks,
+ * the paper's evaluation (Sec. 4, Tab. "operations": the matmul row with a ReLU post-op;
+ * App. "Per-task results": the matmul-with-activation tasks,
  * matrix-vector product, FFN-shaped layers).  The paper fixes no GEMM problem
  * statement; the definition above is the textbook one.
  *
@@ -39,8 +39,8 @@ typedef enum { GEMM_ROW_MAJOR = 0, GEMM_COL_MAJOR = 1 } gemm_layout_t;
  * output column), before the activation.
  *   GELU_ERF (t) = t/2 * (1 + erf(t / sqrt 2))
  *   GELU_TANH(t) = t/2 * (1 + tanh(sqrt(2/pi) * (t + 0.044715 t^3)))
- * The last four are the post-ops of the paper's "matmul + Swish + scaling" and "GEMM +
- * sigmoid + scaling + residual add" tasks (App. "Per-task results"), read as the
+ * The last four are the post-ops of two of the paper's tasks, the matmul followed by Swish and a
+ * scaling and the GEMM followed by sigmoid, scaling and a residual add (App. "Per-task results"), read as the
  * element-wise formulas their names spell out, with sigma(t) = 1 / (1 + exp(-t)) and
  * c = gemm_desc_t.scale:
  *   SWISH_SCALE(t)            = c * t * sigma(t)
@@ -190,8 +190,8 @@ int gemm_autotune_clear(void);
  * Split-K: for products with few output tiles and a long K (too few tiles to occupy the 256
  * CUs), K is cut into `splits` equal slices that are multiplied side by side into fp32
  * partial results in a caller-provided workspace, and a second kernel adds the slices (in
- * a fixed order), applies the epilogue and writes C.  This is the "global coordination,
- * multi-pass with synchronisation" level of the paper's taxonomy (Sec. 3.2, d_sync = 3).
+ * a fixed order), applies the epilogue and writes C.  This is the highest synchronisation level of the paper's taxonomy (Sec. 3.2, d_sync = 3:
+ * several passes with a device-wide synchronisation between them).
  *
  * gemm_create_splitk - as gemm_create, for batch == 1 problems the matrix-core kernels can
  *   take (16-bit or fp8 operands, K-contiguous A and B, every slice a whole number of 16-byte pieces).  splits >= 1, or

@@ -14,8 +14,8 @@
  *   y[b,i,j] = act(t[b,i,j])               act in {id, relu, gelu_erf, gelu_tanh,
  *                                                  swish_scale, sigmoid_scale_residual}
  *
- * The last two are the post-ops of the paper's "matmul + Swish + scaling" and "GEMM +
- * sigmoid + scaling + residual add" tasks (App. "Per-task results").  The paper gives
+ * The last two are the post-ops of two of the paper's tasks: matmul followed by Swish and a
+ * scaling, GEMM followed by sigmoid, scaling and a residual add (App. "Per-task results").  The paper gives
  * only the names; they are read here as the element-wise formulas the names spell out,
  * with sigma(t) = 1 / (1 + exp(-t)) and a scalar scale c:
  *   swish_scale(t)            = c * t * sigma(t)

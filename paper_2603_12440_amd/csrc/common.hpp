@@ -92,8 +92,8 @@ __device__ __forceinline__ float gelu_tanh_f32(float t) {
 __device__ __forceinline__ float sigmoid_f32(float t) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t));
 }
-// The post-ops of the paper's "matmul + Swish + scaling" and "GEMM + sigmoid + scaling +
-// residual add" tasks (App. "Per-task results"); c is the descriptor's scale.
+// The post-ops of two of the paper's tasks: matmul followed by Swish and a scaling, GEMM followed by
+// sigmoid, scaling and a residual add (App. "Per-task results"); c is the descriptor's scale.
 __device__ __forceinline__ float swish_scale_f32(float t, float c) { return c * (t * sigmoid_f32(t)); }
 __device__ __forceinline__ float sigmoid_scale_residual_f32(float t, float c) {
   return fmaf(c, sigmoid_f32(t), t);
