@@ -526,6 +526,8 @@ int fill_launch_shape(gemm_plan& pl) {
     }
     pl.group_m = (int)(tm < 8 ? tm : 8);
     pl.xcd_remap = ((tm * tn) % 8 == 0) ? 1 : 0;
+    // a batch on persistent workgroups: whole problems per XCD (their tiles share panels)
+    if (c.persist && d.batch > 1 && (tm * tn * d.batch) % 8 == 0 && wgs % 8 == 0) pl.xcd_remap = 2;
   } else if (c.kind == KIND_SKINNY_PANEL) {
     pl.grid = dim3((unsigned)((d.N + c.bn - 1) / c.bn), (unsigned)d.batch, 1);
   } else {

@@ -147,6 +147,12 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   int batch = PERSIST ? 0 : (int)blockIdx.y;
   const int n_tiles = p.tiles_m * p.tiles_n;
   const int total_tiles = PERSIST ? n_tiles * p.batches : n_tiles;
+  // A batch on persistent workgroups (xcd_remap == 2; grid and tile count multiples of 8): the 8 XCDs
+  // (round-robin dispatch: XCD = tile id mod 8) each take a contiguous run of the problems, so that the
+  // tiles of one problem, which share its panels, meet in one L2 instead of fetching them 8 times.
+  auto logical_tile = [&](int vid) __attribute__((always_inline)) {
+    return p.xcd_remap == 2 ? (vid & 7) * (total_tiles >> 3) + (vid >> 3) : vid;
+  };
 
   // ---- global -> LDS addressing (as in mfma_kernel.hpp, with this kernel's swizzle) -------
   // Load q of this wave fills LDS bytes [slab + (wave*LOADS + q)*1024, +1024): lane l writes
@@ -161,8 +167,9 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
   // each epilogue, so that they need not stay in registers across it.)  Leaves ld_a / ld_b at slab `kt`.
   auto load_tile = [&](int vid, int ln, int kt) __attribute__((always_inline)) {
     int tm, tn;
-    const int lb = PERSIST ? vid / n_tiles : batch;          // the problem this tile belongs to
-    tile_coords(p, PERSIST ? vid - lb * n_tiles : vid, n_tiles, tm, tn);
+    const int lid = PERSIST ? logical_tile(vid) : vid;
+    const int lb = PERSIST ? lid / n_tiles : batch;          // the problem this tile belongs to
+    tile_coords(p, PERSIST ? lid - lb * n_tiles : vid, n_tiles, tm, tn);
     const int r0 = tm * BM, c0 = tn * BN;
     ld_a = (const char*)((const T*)p.A + (int64_t)lb * p.stride_a + (int64_t)r0 * p.lda) + (int64_t)kt * ROWB;
     ld_b = (const char*)((const T*)p.B + (int64_t)lb * p.stride_b + (int64_t)c0 * p.ldb) + (int64_t)kt * ROWB;
@@ -795,8 +802,9 @@ __global__ __launch_bounds__(64 * WM * WN) void mfma16_gemm_kernel(MfmaArgs p) {
     set_prio(0);
     wait_lgkmcnt<0>();
     int tm, tn;
-    batch = vid / n_tiles;
-    tile_coords(p, vid - batch * n_tiles, n_tiles, tm, tn);
+    const int lid = logical_tile(vid);
+    batch = lid / n_tiles;
+    tile_coords(p, lid - batch * n_tiles, n_tiles, tm, tn);
     epilogue(tm * BM, tn * BN);
     if (!last) {
       // the lane-dependent offsets and addresses are derived afresh here (from an opaque copy of the

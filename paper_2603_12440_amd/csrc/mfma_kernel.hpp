@@ -29,7 +29,8 @@ struct MfmaArgs {
   float scale;                 // scalar of the *_scale activations
   int tiles_m, tiles_n;        // ceil(M/BM), ceil(N/BN)
   int group_m;                 // tile rows per scheduling group
-  int xcd_remap;               // 1: spread consecutive tile ids within one XCD
+  int xcd_remap;               // 1: spread consecutive tile ids within one XCD; 2 (persistent workgroups, a batch):
+                               // consecutive problems of the batch within one XCD
   int c_cached;                // 1: fp32 C is read again right away (split-K partials): ordinary stores
   int batches;                 // problems in the batch (persistent workgroups walk over the tiles of all of them)
 };
@@ -124,7 +125,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void tile_coords(const MfmaArgs& p, int wg, int n_wg,
                                             int& tm, int& tn) {
   int id = wg;
-  if (p.xcd_remap) {
+  if (p.xcd_remap == 1) {
     const int per = n_wg >> 3;                 // n_wg is a multiple of 8 when remap is on
     id = (wg & 7) * per + (wg >> 3);
   }
