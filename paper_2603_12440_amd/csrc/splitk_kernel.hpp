@@ -5,7 +5,8 @@
 // (slice 0 first), so the result does not depend on which workgroup finished first.
 //
 // Streaming kernel: every lane takes 4 consecutive columns of one row (16-byte loads from
-// each slice), a workgroup 1024 consecutive elements of the row-major partials.
+// each slice, eight slices requested at a time), a workgroup 1024 consecutive elements of the
+// row-major partials.
 #pragma once
 
 #include "common.hpp"
@@ -33,12 +34,25 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitKReduceArgs p) 
   const float* src = p.ws + i * p.N + j;
   float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   const bool full = (j + 3 < p.N) && (p.N % 4 == 0);       // whole, 16-byte aligned quad
-  for (int s = 0; s < p.splits; ++s) {
-    if (full) {
+  if (full) {
+    // eight slices' loads in flight at a time, added in slice order
+    int s = 0;
+    for (; s + 8 <= p.splits; s += 8) {
+      f32x4_t w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) w[u] = __builtin_nontemporal_load((const f32x4_t*)(src + (s + u) * slice));
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] += w[u][e];
+    }
+    for (; s < p.splits; ++s) {
       const f32x4_t w = __builtin_nontemporal_load((const f32x4_t*)(src + s * slice));
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] += w[e];
-    } else {
+    }
+  } else {
+    for (int s = 0; s < p.splits; ++s) {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (j + e < p.N) v[e] += src[s * slice + e];
